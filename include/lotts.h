@@ -1,0 +1,133 @@
+/*
+ * lotts.h -- C ABI of the MI355X (gfx950) speculative verification step run across B
+ * concurrent reasoning branches: the hot path of latency-optimal test-time scaling
+ * ("Faster and Better LLMs via Latency-Aware Test-Time Scaling", arXiv 2505.19634).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or synchronises; work is enqueued on `stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and outputs are fully overwritten.
+ *   - Return value: LOTTS_OK or a negative lotts_status.  All argument checks run on the
+ *     host before anything is launched; a failed call launches nothing.
+ *   - Scratch memory is passed in as `workspace`; the *_workspace_bytes queries say how much.
+ *     Its contents need not be initialised and are undefined afterwards.  Calls that share a
+ *     workspace must be ordered on one stream.
+ */
+#ifndef LOTTS_H
+#define LOTTS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOTTS_OK = 0,
+    LOTTS_ERR_NULL = -1,       /* a required pointer is NULL */
+    LOTTS_ERR_SHAPE = -2,      /* sizes or strides the kernels cannot take */
+    LOTTS_ERR_DTYPE = -3,      /* unknown element type */
+    LOTTS_ERR_WORKSPACE = -4,  /* workspace smaller than *_workspace_bytes */
+    LOTTS_ERR_LAUNCH = -5      /* the HIP runtime refused a launch */
+} lotts_status;
+
+typedef enum { LOTTS_F32 = 0, LOTTS_BF16 = 1 } lotts_dtype;
+
+/* Human-readable text for a status code; never NULL. */
+const char *lotts_strerror(int status);
+
+/*
+ * Geometry of one verify_attention call.
+ * R = k + 1 query rows per branch: the k draft tokens (Section 3.3: draft length gamma) plus
+ * the bonus position.  Query head h reads KV head h / (Hq / Hkv).
+ * Strides are in ELEMENTS; the innermost D elements of every row are contiguous.
+ * K and V of the same segment use the same strides.
+ */
+typedef struct {
+    int32_t B;        /* concurrent branches (Section 3.2, branch-wise parallelism), >= 1 */
+    int32_t k;        /* draft tokens per branch (sequence-wise parallelism), >= 0 */
+    int32_t Hq, Hkv;  /* query / KV heads, Hq % Hkv == 0 */
+    int32_t D;        /* head dimension: 64 or 128 */
+    int32_t P;        /* tokens of the prompt prefix shared by all branches, >= 0 */
+    int32_t Lmax;     /* allocated private tokens per branch, >= k + 1 */
+    int32_t dtype;    /* lotts_dtype of Q, K, V and O */
+    float scale;      /* softmax scale; 0 selects 1 / sqrt(D) */
+    int64_t q_stride_b, q_stride_r, q_stride_h;              /* Q  [B][R][Hq][D] */
+    int64_t kpre_stride_h, kpre_stride_t;                    /* Kpre, Vpre [Hkv][P][D] */
+    int64_t kpriv_stride_b, kpriv_stride_h, kpriv_stride_t;  /* Kpriv, Vpriv [B][Hkv][Lmax][D] */
+    int64_t o_stride_b, o_stride_r, o_stride_h;              /* O  [B][R][Hq][D] */
+} lotts_attn_desc;
+
+/* Bytes of workspace verify_attention needs for this geometry (0 if the descriptor is invalid). */
+size_t verify_attention_workspace_bytes(const lotts_attn_desc *desc);
+
+/*
+ * verify_attention -- the target model's causal attention for the k + 1 new positions of
+ * every branch (Section 2, speculative decoding: the target verifies the drafts in one
+ * parallel forward; Section 3.1: the step is bound by loading the KV cache), one layer.
+ *
+ *   O[b][i][h][:] = sum_j softmax_j(scale * <Q[b][i][h], K_j>) * V_j
+ * over the keys visible to row i of branch b: all P prefix keys, then the first
+ * priv_len[b] - k + i private keys of branch b (the last k + 1 private positions are the new
+ * tokens themselves; row i sees itself and the earlier ones).  The prefix K/V exist once and
+ * are read from HBM once, whatever B is.
+ *
+ *   Q      [B][R][Hq][D]        dtype, strides from desc
+ *   Kpre, Vpre   [Hkv][P][D]    dtype; may be NULL iff P == 0
+ *   Kpriv, Vpriv [B][Hkv][Lmax][D] dtype
+ *   priv_len [B] int32: private tokens of branch b INCLUDING its k + 1 new tokens.
+ *            Contract k + 1 <= priv_len[b] <= Lmax.  It is device data and is not checked on
+ *            the host: the kernels clamp it into that range, so nothing is read out of
+ *            bounds, but the rows of an offending branch are then unspecified.
+ *   O      [B][R][Hq][D] dtype, out
+ *   lse    [B][R][Hq] fp32, out, may be NULL: natural-log sum of exp of the scaled scores
+ *   workspace: >= verify_attention_workspace_bytes(desc), 256-byte aligned
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs are
+ * computed in fp32 throughout.
+ */
+int verify_attention(const lotts_attn_desc *desc, const void *Q, const void *Kpre, const void *Vpre,
+                     const void *Kpriv, const void *Vpriv, const int32_t *priv_len, void *O, float *lse,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace spec_accept needs (0 if the sizes are invalid). */
+size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V);
+
+/*
+ * spec_accept -- lossless speculative-sampling acceptance per branch (the rule of the works
+ * Section 2 cites for speculative decoding): draft token x_j is accepted iff
+ * u_j < min(1, p_j(x_j) / q_j(x_j)), tested exactly as u_j * q_j(x_j) < p_j(x_j) in fp64;
+ * accept_len[b] = n counts the drafts accepted before the first rejection.  The next token is
+ * drawn from norm(max(0, p_n - q_n)) if n < k, from p_k otherwise, by inverting an integer
+ * fixed-point CDF: w_v = trunc(r_v * 2^40), Z = sum_v w_v, T = floor(trunc(u[b][k] * 2^24) * Z
+ * / 2^24), token = first v with w_0 + ... + w_v > T.  Integer sums make the result the same
+ * for any reduction order.  If the residual has no mass the row p_n itself is sampled; if that
+ * has none either, next_token = -1.
+ *
+ *   p [B][k+1][V] fp32  target probabilities (finite, >= 0)
+ *   q [B][k][V]   fp32  draft probabilities; NULL iff k == 0
+ *   draft [B][k]  int32 draft tokens in [0, V) (the kernel clamps); NULL iff k == 0
+ *   u [B][k+1]    fp32  uniforms in [0, 1)
+ *   accept_len [B] int32 out, in [0, k];  next_token [B] int32 out, in [0, V) or -1
+ *   workspace: >= spec_accept_workspace_bytes(B, k, V), 256-byte aligned
+ */
+int spec_accept(int32_t B, int32_t k, int32_t V, const float *p, const float *q, const int32_t *draft,
+                const float *u, int32_t *accept_len, int32_t *next_token, void *workspace,
+                size_t workspace_bytes, void *stream);
+
+/*
+ * majority_vote -- the answer most branches agree on (Section 1 and Section 4.1: branches are
+ * aggregated by majority voting), for N independent questions at once.
+ *
+ *   answers [N][B] int32: answer id of each branch; ids < 0 mean "no answer" and do not count
+ *   winner [N], winner_count [N] int32 out: the id with the most votes and its votes; ties go
+ *   to the id whose first occurrence has the smallest branch index; (-1, 0) if no branch
+ *   answered.  1 <= B <= 4096.
+ */
+int majority_vote(int32_t N, int32_t B, const int32_t *answers, int32_t *winner, int32_t *winner_count,
+                  void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOTTS_H */

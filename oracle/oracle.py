@@ -1,0 +1,123 @@
+"""ctypes loader and numpy marshalling for the C oracle.  Test infrastructure only."""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lotts_oracle.c")
+_LIB = os.path.join(_HERE, "liblotts_oracle.so")
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = True) -> str:
+    """Compile lotts_oracle.c with gcc (OpenMP only spreads independent outputs over threads)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        c_int, c_dbl, vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        lib.oracle_verify_attention.restype = c_int
+        lib.oracle_verify_attention.argtypes = [c_int] * 8 + [c_dbl] + [vp] * 8
+        lib.oracle_spec_accept.restype = c_int
+        lib.oracle_spec_accept.argtypes = [c_int] * 3 + [vp] * 6
+        lib.oracle_majority_vote.restype = c_int
+        lib.oracle_majority_vote.argtypes = [c_int] * 2 + [vp] * 3
+        _lib = lib
+    return _lib
+
+
+def set_threads(n: int) -> None:
+    """Limit the OpenMP team (libgomp) of later oracle calls."""
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
+def n_threads() -> int:
+    return int(ctypes.CDLL("libgomp.so.1").omp_get_max_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _kv(a: np.ndarray) -> Tuple[np.ndarray, int]:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        return a, F32
+    if a.dtype == np.uint16:
+        return a, BF16
+    raise TypeError("Q/K/V must be float32 or uint16 (bf16 bit patterns), got %s" % a.dtype)
+
+
+def verify_attention(Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, scale: float = 0.0, want_lse: bool = True):
+    """fp64 attention of the k+1 new rows of each branch.  Shapes as in lotts_oracle.c.
+    Returns (O [B][R][Hq][D] float64, lse [B][R][Hq] float64 or None)."""
+    Q, dt = _kv(Q)
+    B, R, Hq, D = Q.shape
+    Kpriv, dt2 = _kv(Kpriv)
+    Vpriv, _ = _kv(Vpriv)
+    _, Hkv, Lmax, _ = Kpriv.shape
+    if Kpre is None or Kpre.shape[1] == 0:
+        P, Kpre, Vpre = 0, None, None
+    else:
+        Kpre, _ = _kv(Kpre)
+        Vpre, _ = _kv(Vpre)
+        P = Kpre.shape[1]
+    assert dt == dt2
+    priv_len = np.ascontiguousarray(priv_len, dtype=np.int32)
+    O = np.empty((B, R, Hq, D), dtype=np.float64)
+    lse = np.empty((B, R, Hq), dtype=np.float64) if want_lse else None
+    rc = _load().oracle_verify_attention(B, R - 1, Hq, Hkv, D, P, Lmax, dt, float(scale), _ptr(Q), _ptr(Kpre),
+                                         _ptr(Vpre), _ptr(Kpriv), _ptr(Vpriv), _ptr(priv_len), _ptr(O), _ptr(lse))
+    if rc != 0:
+        raise ValueError("oracle_verify_attention rejected the call (rc=%d)" % rc)
+    return O, lse
+
+
+def spec_accept(p, q, draft, u):
+    """Returns (accept_len [B] int32, next_token [B] int32)."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    B, R, V = p.shape
+    k = R - 1
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    assert u.shape == (B, R)
+    if k > 0:
+        q = np.ascontiguousarray(q, dtype=np.float32)
+        draft = np.ascontiguousarray(draft, dtype=np.int32)
+        assert q.shape == (B, k, V) and draft.shape == (B, k)
+    else:
+        q, draft = None, None
+    n = np.empty((B,), dtype=np.int32)
+    t = np.empty((B,), dtype=np.int32)
+    rc = _load().oracle_spec_accept(B, k, V, _ptr(p), _ptr(q), _ptr(draft), _ptr(u), _ptr(n), _ptr(t))
+    if rc != 0:
+        raise ValueError("oracle_spec_accept rejected the call (rc=%d)" % rc)
+    return n, t
+
+
+def majority_vote(answers):
+    """answers [N][B] (or [B]) int32 -> (winner [N], count [N])."""
+    a = np.ascontiguousarray(answers, dtype=np.int32)
+    if a.ndim == 1:
+        a = a[None, :]
+    N, B = a.shape
+    w = np.empty((N,), dtype=np.int32)
+    c = np.empty((N,), dtype=np.int32)
+    rc = _load().oracle_majority_vote(N, B, _ptr(a), _ptr(w), _ptr(c))
+    if rc != 0:
+        raise ValueError("oracle_majority_vote rejected the call (rc=%d)" % rc)
+    return w, c
