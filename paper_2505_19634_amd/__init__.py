@@ -1,0 +1,9 @@
+"""MI355X-native speculative verification step across B reasoning branches (gfx950, HIP).
+
+The product is liblotts.so (csrc/, C ABI in include/lotts.h); this package is its thin
+binding.  Importing it loads the library and fails loudly if it has not been built.
+"""
+from .binding import (AttnDesc, LottsError, load, strerror, verify_attention, spec_accept,  # noqa: F401
+                      majority_vote, make_attn_desc, EXPORTS, LIB_PATH)
+
+load()

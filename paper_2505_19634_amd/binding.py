@@ -1,0 +1,207 @@
+"""Thin Python binding of liblotts.so: argument marshalling only.
+
+torch supplies device memory and the current stream; every step of the verify path runs in
+the library's HIP kernels.  There is no fallback: if the library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblotts.so")
+
+LOTTS_F32, LOTTS_BF16 = 0, 1
+
+EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
+           "spec_accept_workspace_bytes", "spec_accept", "majority_vote")
+
+
+class AttnDesc(ctypes.Structure):
+    """Mirror of lotts_attn_desc."""
+    _fields_ = [("B", ctypes.c_int32), ("k", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("P", ctypes.c_int32), ("Lmax", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_r", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("kpre_stride_h", ctypes.c_int64), ("kpre_stride_t", ctypes.c_int64),
+                ("kpriv_stride_b", ctypes.c_int64), ("kpriv_stride_h", ctypes.c_int64),
+                ("kpriv_stride_t", ctypes.c_int64),
+                ("o_stride_b", ctypes.c_int64), ("o_stride_r", ctypes.c_int64), ("o_stride_h", ctypes.c_int64)]
+
+
+class LottsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("liblotts.so is not built: run paper_2505_19634_amd/build.py "
+                              "(or __graft_entry__.build())")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lib.lotts_strerror.restype = ctypes.c_char_p
+        lib.lotts_strerror.argtypes = [ctypes.c_int]
+        lib.verify_attention_workspace_bytes.restype = sz
+        lib.verify_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+        lib.verify_attention.restype = ctypes.c_int
+        lib.verify_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8 + [vp, sz, vp]
+        lib.spec_accept_workspace_bytes.restype = sz
+        lib.spec_accept_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.spec_accept.restype = ctypes.c_int
+        lib.spec_accept.argtypes = [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
+        lib.majority_vote.restype = ctypes.c_int
+        lib.majority_vote.argtypes = [i32, i32, vp, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load().lotts_strerror(int(status)).decode()
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+_workspaces: Dict[Tuple[str, int], torch.Tensor] = {}
+
+
+def _workspace(kind: str, device: torch.device, nbytes: int) -> torch.Tensor:
+    """One cached scratch tensor per entry point and device, grown on demand."""
+    key = (kind, device.index if device.index is not None else torch.cuda.current_device())
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def make_attn_desc(Q: torch.Tensor, Kpre: Optional[torch.Tensor], Kpriv: torch.Tensor, O: torch.Tensor,
+                   scale: float = 0.0) -> AttnDesc:
+    B, R, Hq, D = Q.shape
+    Bk, Hkv, Lmax, Dk = Kpriv.shape
+    if Bk != B or Dk != D:
+        raise ValueError("Q %s and Kpriv %s disagree" % (tuple(Q.shape), tuple(Kpriv.shape)))
+    if Q.dtype == torch.bfloat16:
+        dt = LOTTS_BF16
+    elif Q.dtype == torch.float32:
+        dt = LOTTS_F32
+    else:
+        raise TypeError("Q/K/V must be bfloat16 or float32")
+    for t in (Q, Kpriv, O) + ((Kpre,) if Kpre is not None else ()):
+        if t.stride(-1) != 1:
+            raise ValueError("the head dimension must be contiguous")
+    d = AttnDesc()
+    d.B, d.k, d.Hq, d.Hkv, d.D, d.Lmax, d.dtype, d.scale = B, R - 1, Hq, Hkv, D, Lmax, dt, float(scale)
+    d.P = 0 if Kpre is None else Kpre.shape[1]
+    d.q_stride_b, d.q_stride_r, d.q_stride_h = Q.stride(0), Q.stride(1), Q.stride(2)
+    d.o_stride_b, d.o_stride_r, d.o_stride_h = O.stride(0), O.stride(1), O.stride(2)
+    d.kpriv_stride_b, d.kpriv_stride_h, d.kpriv_stride_t = Kpriv.stride(0), Kpriv.stride(1), Kpriv.stride(2)
+    if Kpre is not None and d.P > 0:
+        d.kpre_stride_h, d.kpre_stride_t = Kpre.stride(0), Kpre.stride(1)
+    return d
+
+
+def verify_attention(Q: torch.Tensor, Kpre: Optional[torch.Tensor], Vpre: Optional[torch.Tensor],
+                     Kpriv: torch.Tensor, Vpriv: torch.Tensor, priv_len: torch.Tensor, *, scale: float = 0.0,
+                     out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                     return_lse: bool = False, workspace: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None):
+    """Q [B][k+1][Hq][D], Kpre/Vpre [Hkv][P][D] or None, Kpriv/Vpriv [B][Hkv][Lmax][D], priv_len [B] int32;
+    all on one GPU.  Returns O [B][k+1][Hq][D] (same dtype), and LSE [B][k+1][Hq] fp32 if asked."""
+    lib = load()
+    if not Q.is_cuda:
+        raise ValueError("verify_attention runs on the GPU only")
+    if Kpre is not None and Kpre.shape[1] == 0:
+        Kpre, Vpre = None, None
+    if Vpriv.stride() != Kpriv.stride() or (Kpre is not None and Vpre.stride() != Kpre.stride()):
+        raise ValueError("K and V of a segment must share strides")
+    if priv_len.dtype != torch.int32:
+        raise TypeError("priv_len must be int32")
+    if out is None:
+        out = torch.empty(Q.shape, dtype=Q.dtype, device=Q.device)
+    if return_lse and lse is None:
+        lse = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    desc = make_attn_desc(Q, Kpre, Kpriv, out, scale)
+    need = lib.verify_attention_workspace_bytes(ctypes.byref(desc))
+    if need == 0:
+        raise LottsError(-2, "verify_attention_workspace_bytes")
+    ws = _workspace("attn", Q.device, need) if workspace is None else workspace
+    rc = lib.verify_attention(ctypes.byref(desc), _ptr(Q), _ptr(Kpre), _ptr(Vpre), _ptr(Kpriv), _ptr(Vpriv),
+                              _ptr(priv_len), _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
+                              _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "verify_attention")
+    return (out, lse) if return_lse else out
+
+
+def spec_accept(p: torch.Tensor, q: Optional[torch.Tensor], draft: Optional[torch.Tensor], u: torch.Tensor, *,
+                accept_len: Optional[torch.Tensor] = None, next_token: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """p [B][k+1][V] fp32, q [B][k][V] fp32, draft [B][k] int32, u [B][k+1] fp32 (contiguous, on the GPU).
+    Returns (accept_len [B] int32, next_token [B] int32)."""
+    lib = load()
+    if not p.is_cuda:
+        raise ValueError("spec_accept runs on the GPU only")
+    B, R, V = p.shape
+    k = R - 1
+    if p.dtype != torch.float32 or u.dtype != torch.float32 or not p.is_contiguous() or not u.is_contiguous():
+        raise TypeError("p and u must be contiguous float32")
+    if tuple(u.shape) != (B, R):
+        raise ValueError("u must be [B][k+1]")
+    if k > 0:
+        if q is None or draft is None or tuple(q.shape) != (B, k, V) or tuple(draft.shape) != (B, k):
+            raise ValueError("q must be [B][k][V] and draft [B][k]")
+        if q.dtype != torch.float32 or draft.dtype != torch.int32 or not q.is_contiguous() or not draft.is_contiguous():
+            raise TypeError("q must be contiguous float32 and draft contiguous int32")
+    else:
+        q, draft = None, None
+    if accept_len is None:
+        accept_len = torch.empty((B,), dtype=torch.int32, device=p.device)
+    if next_token is None:
+        next_token = torch.empty((B,), dtype=torch.int32, device=p.device)
+    need = lib.spec_accept_workspace_bytes(B, k, V)
+    if need == 0:
+        raise LottsError(-2, "spec_accept_workspace_bytes")
+    ws = _workspace("accept", p.device, need) if workspace is None else workspace
+    rc = lib.spec_accept(B, k, V, _ptr(p), _ptr(q), _ptr(draft), _ptr(u), _ptr(accept_len), _ptr(next_token),
+                         _ptr(ws), ws.numel() * ws.element_size(), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "spec_accept")
+    return accept_len, next_token
+
+
+def majority_vote(answers: torch.Tensor, *, winner: Optional[torch.Tensor] = None,
+                  winner_count: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """answers [N][B] (or [B]) int32 on the GPU -> (winner [N], winner_count [N]) int32."""
+    lib = load()
+    if not answers.is_cuda:
+        raise ValueError("majority_vote runs on the GPU only")
+    if answers.dim() == 1:
+        answers = answers[None, :]
+    if answers.dtype != torch.int32 or not answers.is_contiguous():
+        raise TypeError("answers must be contiguous int32")
+    N, B = answers.shape
+    if winner is None:
+        winner = torch.empty((N,), dtype=torch.int32, device=answers.device)
+    if winner_count is None:
+        winner_count = torch.empty((N,), dtype=torch.int32, device=answers.device)
+    rc = lib.majority_vote(N, B, _ptr(answers), _ptr(winner), _ptr(winner_count), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "majority_vote")
+    return winner, winner_count

@@ -1,0 +1,56 @@
+// Shared by the HIP translation units of liblotts.so: status codes, launch checking and
+// wavefront helpers.  gfx950 only (64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "lotts.h"
+
+namespace lotts {
+
+constexpr int kWave = 64;
+// MI355X: 256 compute units in 8 XCDs.  Launch plans are sized for this part and do not depend
+// on the device the process happens to see, so workspace queries agree everywhere.
+constexpr int kNumCU = 256;
+constexpr int kNumXCD = 8;
+
+inline int check_launch() {
+    return hipGetLastError() == hipSuccess ? LOTTS_OK : LOTTS_ERR_LAUNCH;
+}
+
+__device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }
+
+__device__ __forceinline__ unsigned long long shfl_down_u64(unsigned long long v, int delta) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = __shfl_down(lo, delta, kWave);
+    hi = __shfl_down(hi, delta, kWave);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, int delta) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = __shfl_up(lo, delta, kWave);
+    hi = __shfl_up(hi, delta, kWave);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long shfl_u64(unsigned long long v, int src) {
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = __shfl(lo, src, kWave);
+    hi = __shfl(hi, src, kWave);
+    return ((unsigned long long)hi << 32) | lo;
+}
+// sum over the wavefront; the total is valid in lane 0
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += shfl_down_u64(v, d);
+    return v;
+}
+// inclusive prefix sum over the wavefront
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        unsigned long long o = shfl_up_u64(v, d);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+}  // namespace lotts

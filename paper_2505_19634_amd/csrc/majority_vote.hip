@@ -1,0 +1,78 @@
+// majority_vote: the answer most branches give (paper Section 1 / Section 4.1: branches are
+// aggregated by majority voting).  One workgroup per question; B is tens to a few thousand
+// ids, so this is a latency-bound O(B^2 / 256) count in LDS.
+#include "lotts_common.h"
+
+namespace lotts {
+
+constexpr int kVoteThreads = 256;
+constexpr int kVoteMaxB = 4096;
+
+__global__ __launch_bounds__(kVoteThreads) void majority_vote_kernel(int B, const int32_t* __restrict__ answers,
+                                                                     int32_t* __restrict__ winner,
+                                                                     int32_t* __restrict__ winner_count) {
+    __shared__ int32_t a[kVoteMaxB];
+    __shared__ unsigned long long best[kVoteThreads / kWave];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const int32_t* row = answers + (size_t)n * B;
+    for (int i = tid; i < B; i += kVoteThreads) a[i] = row[i];
+    __syncthreads();
+    // Only the first occurrence of an id competes.  Key = (votes << 32) | (2^32 - 1 - index):
+    // the maximum is the largest vote count, and among equal counts the smallest index.
+    unsigned long long key = 0;
+    for (int i = tid; i < B; i += kVoteThreads) {
+        const int32_t ai = a[i];
+        if (ai < 0) continue;
+        int votes = 0;
+        bool first = true;
+        for (int j = 0; j < B; ++j) {
+            const bool same = (a[j] == ai);
+            votes += same;
+            first = first && !(same && j < i);
+        }
+        if (first) {
+            const unsigned long long kk = ((unsigned long long)votes << 32) | (0xFFFFFFFFu - (unsigned)i);
+            key = kk > key ? kk : key;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned long long o = shfl_down_u64(key, d);
+        key = o > key ? o : key;
+    }
+    if ((tid & (kWave - 1)) == 0) best[tid / kWave] = key;
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < kVoteThreads / kWave; ++w) key = best[w] > key ? best[w] : key;
+        if (key == 0) {
+            winner[n] = -1;
+            winner_count[n] = 0;
+        } else {
+            winner[n] = a[0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFu)];
+            winner_count[n] = (int32_t)(key >> 32);
+        }
+    }
+}
+
+}  // namespace lotts
+
+extern "C" int majority_vote(int32_t N, int32_t B, const int32_t* answers, int32_t* winner, int32_t* winner_count,
+                             void* stream) {
+    if (!answers || !winner || !winner_count) return LOTTS_ERR_NULL;
+    if (N < 1 || B < 1 || B > lotts::kVoteMaxB) return LOTTS_ERR_SHAPE;
+    hipLaunchKernelGGL(lotts::majority_vote_kernel, dim3(N), dim3(lotts::kVoteThreads), 0, (hipStream_t)stream, B,
+                       answers, winner, winner_count);
+    return lotts::check_launch();
+}
+
+extern "C" const char* lotts_strerror(int status) {
+    switch (status) {
+        case LOTTS_OK: return "ok";
+        case LOTTS_ERR_NULL: return "a required pointer is NULL";
+        case LOTTS_ERR_SHAPE: return "unsupported sizes, strides or alignment";
+        case LOTTS_ERR_DTYPE: return "unsupported element type";
+        case LOTTS_ERR_WORKSPACE: return "workspace too small";
+        case LOTTS_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown lotts status";
+    }
+}

@@ -1,0 +1,618 @@
+// verify_attention: causal attention of the k + 1 new positions of every branch against the
+// branch's KV cache, which sits behind a prompt prefix shared by all branches (paper
+// Section 3.2: B branches of one question; Section 2: the target model verifies the drafts in
+// one parallel forward; Section 3.1: the step is bound by loading the KV cache).
+//
+// bf16 path (MFMA, gfx950):
+//   attn_partial_kernel   one launch over "work items".  An item is a range of 32-key tiles of
+//       one KV segment (the shared prefix of a KV head, or one branch's private cache) and a
+//       stack of up to 32*NQT query rows that all read those keys:
+//         - private item: the G*R rows (G = Hq/Hkv query heads x R = k+1 positions) of one
+//           branch and KV head;
+//         - prefix item: rows of SEVERAL branches stacked, so a prefix tile is fetched once per
+//           row stack instead of once per branch.
+//       The 4 wavefronts of a workgroup take tiles round-robin; each streams its own K tile
+//       straight into MFMA operand registers and its V tile through a private LDS slab (read
+//       back with the transposing LDS load), keeps flash-style running (max, sum, O) state, and
+//       the 4 states are merged through LDS in a fixed order.  The item's un-normalised
+//       partial goes to the workspace.
+//   attn_merge_kernel     log-sum-exp merge of the prefix and private partials, normalise,
+//       convert, store O (and LSE).
+// fp32 path: attn_f32_kernel, plain fp32 VALU arithmetic, one workgroup per output row; it
+// exists for exactness checks on small fp32 problems, not for speed.
+#include "lotts_common.h"
+
+namespace lotts {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kTile = 32;      // keys per tile = M of one 32x32x16 MFMA
+constexpr int kRowTile = 32;   // query rows per row tile = N of the MFMA
+constexpr int kMaxSplit = 64;
+
+struct AttnPlan {
+    int nqt;            // row tiles per item: 1 or 2
+    int n_rg_priv;      // row groups per (branch, KV head)
+    int n_rg_pre;       // row groups per KV head over all branches' stacked rows
+    int nsplit_priv;    // key splits of a private segment
+    int nsplit_pre;     // key splits of the prefix (0 if P == 0)
+    int nslots;         // partials per output row
+    int n_pre_items, n_priv_items;
+};
+
+struct AttnParams {
+    const void *Q, *Kpre, *Vpre, *Kpriv, *Vpriv;
+    const int32_t* priv_len;
+    float* part_o;   // [Hkv][B*GR][nslots][D]
+    float* part_ml;  // [Hkv][B*GR][nslots][2]  (running max in log2 units, sum)
+    void* O;
+    float* lse;
+    int B, k, R, Hq, Hkv, G, GR, D, P, Lmax;
+    float scale_log2;  // scale * log2(e)
+    long long q_stride_b, q_stride_r, q_stride_h;
+    long long kpre_stride_h, kpre_stride_t;
+    long long kpriv_stride_b, kpriv_stride_h, kpriv_stride_t;
+    long long o_stride_b, o_stride_r, o_stride_h;
+    AttnPlan plan;
+};
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Launch plan.  Depends on the descriptor only (never on device data), so the workspace query
+// and the launch agree.  Target: about two 4-wave workgroups per compute unit.
+static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
+    AttnPlan pl;
+    const int GR = (d.Hq / d.Hkv) * (d.k + 1);
+    pl.nqt = GR > kRowTile ? 2 : 1;
+    const int rows_per_item = kRowTile * pl.nqt;
+    pl.n_rg_priv = ceil_div(GR, rows_per_item);
+    pl.n_rg_pre = ceil_div(d.B * GR, rows_per_item);
+    const int tiles_priv = ceil_div(d.Lmax, kTile);
+    const long long base = (long long)d.B * d.Hkv * pl.n_rg_priv;
+    long long want = (2LL * kNumCU + base - 1) / base;
+    int max_split = tiles_priv / kAttnWaves;  // at least one tile per wavefront
+    if (max_split > kMaxSplit) max_split = kMaxSplit;
+    if (max_split < 1) max_split = 1;
+    pl.nsplit_priv = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
+    if (d.P > 0) {
+        const int tiles_pre = ceil_div(d.P, kTile);
+        const int tiles_per_item = ceil_div(tiles_priv, pl.nsplit_priv);
+        int s = (tiles_pre + tiles_per_item / 2) / tiles_per_item;
+        int cap = tiles_pre / kAttnWaves;
+        if (cap > kMaxSplit) cap = kMaxSplit;
+        if (s > cap) s = cap;
+        pl.nsplit_pre = s < 1 ? 1 : s;
+    } else {
+        pl.nsplit_pre = 0;
+    }
+    pl.nslots = pl.nsplit_pre + pl.nsplit_priv;
+    pl.n_pre_items = d.Hkv * pl.n_rg_pre * pl.nsplit_pre;
+    pl.n_priv_items = d.B * d.Hkv * pl.n_rg_priv * pl.nsplit_priv;
+    return pl;
+}
+
+static inline size_t part_o_elems(const lotts_attn_desc& d, const AttnPlan& pl) {
+    return (size_t)d.Hkv * d.B * (d.Hq / d.Hkv) * (d.k + 1) * pl.nslots * d.D;
+}
+static inline size_t part_ml_elems(const lotts_attn_desc& d, const AttnPlan& pl) {
+    return (size_t)d.Hkv * d.B * (d.Hq / d.Hkv) * (d.k + 1) * pl.nslots * 2;
+}
+
+__device__ __forceinline__ bf16x8 load_bf16x8(const __bf16* ptr) {
+    return *reinterpret_cast<const bf16x8*>(ptr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 partial attention
+// ---------------------------------------------------------------------------------------------
+template <int D, int NQT>
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const AttnParams prm) {
+    constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
+    constexpr int DB = D / 32;             // 32-wide blocks of the head dimension
+    constexpr int VSTRIDE = D * 2 + 64;    // bytes per key row of the V slab (pad: no bank conflicts)
+    constexpr int SLAB = kTile * VSTRIDE;  // bytes of V slab per wavefront
+    constexpr int OSTRIDE = D + 4;         // floats per row of the merge buffer
+    constexpr int MERGE_BYTES = kRowTile * OSTRIDE * 4;
+    constexpr int LDS_MAIN = (kAttnWaves * SLAB > MERGE_BYTES) ? kAttnWaves * SLAB : MERGE_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_MAIN];
+    __shared__ float sh_m[kAttnWaves][kRowTile * NQT];
+    __shared__ float sh_l[kAttnWaves][kRowTile * NQT];
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int ln = lane & 31;   // MFMA column (query row) / A row (key or d) owned by this lane
+    const int hh = lane >> 5;   // which half of each 16-wide k block this lane holds
+    const AttnPlan& pl = prm.plan;
+    const int GR = prm.GR;
+
+    // ---- decode the work item ----
+    int id = blockIdx.x;
+    int kvh, split, nsplit, rho0, rho_end, seg_len, slot, causal_base;
+    const __bf16 *Kseg, *Vseg;
+    long long stride_t;
+    if (id < pl.n_pre_items) {
+        kvh = id % prm.Hkv;
+        int rest = id / prm.Hkv;
+        split = rest % pl.nsplit_pre;
+        const int rg = rest / pl.nsplit_pre;
+        nsplit = pl.nsplit_pre;
+        rho0 = rg * kRowTile * NQT;
+        rho_end = min(prm.B * GR, rho0 + kRowTile * NQT);
+        seg_len = prm.P;
+        causal_base = prm.P;  // every row sees the whole prefix
+        Kseg = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
+        Vseg = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
+        stride_t = prm.kpre_stride_t;
+        slot = split;
+    } else {
+        id -= pl.n_pre_items;
+        kvh = id % prm.Hkv;
+        int rest = id / prm.Hkv;
+        split = rest % pl.nsplit_priv;
+        rest /= pl.nsplit_priv;
+        const int rg = rest % pl.n_rg_priv;
+        const int b = rest / pl.n_rg_priv;
+        nsplit = pl.nsplit_priv;
+        rho0 = b * GR + rg * kRowTile * NQT;
+        rho_end = min((b + 1) * GR, rho0 + kRowTile * NQT);
+        int L = prm.priv_len[b];
+        L = L < prm.R ? prm.R : (L > prm.Lmax ? prm.Lmax : L);
+        seg_len = L;
+        causal_base = L - prm.k;  // row at position r sees private keys [0, L - k + r)
+        const long long off = (long long)b * prm.kpriv_stride_b + (long long)kvh * prm.kpriv_stride_h;
+        Kseg = (const __bf16*)prm.Kpriv + off;
+        Vseg = (const __bf16*)prm.Vpriv + off;
+        stride_t = prm.kpriv_stride_t;
+        slot = pl.nsplit_pre + split;
+    }
+    const bool is_private = blockIdx.x >= pl.n_pre_items;
+    const int ntiles = (seg_len + kTile - 1) / kTile;
+    const int t_lo = (int)((long long)split * ntiles / nsplit);
+    const int t_hi = (int)((long long)(split + 1) * ntiles / nsplit);
+
+    // ---- Q fragments (B operand of S^T = K Q^T: lane = query row ln, 8 contiguous d) ----
+    bf16x8 qf[NQT][KS];
+    int lim[NQT];  // keys of this segment visible to this lane's query row
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+        const int rho = rho0 + t * kRowTile + ln;
+        const bool valid = rho < rho_end;
+        const int rc = valid ? rho : rho0;
+        const int b = rc / GR, rl = rc - b * GR;
+        const int r = rl / prm.G, hg = rl - r * prm.G;
+        lim[t] = is_private ? causal_base + r : causal_base;
+        const __bf16* qp = (const __bf16*)prm.Q + (long long)b * prm.q_stride_b + (long long)r * prm.q_stride_r +
+                           (long long)(kvh * prm.G + hg) * prm.q_stride_h;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 v = load_bf16x8(qp + (2 * s + hh) * 8);
+            if (!valid) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = (__bf16)0.0f;
+            }
+            qf[t][s] = v;
+        }
+    }
+
+    // ---- running state ----
+    f32x16 oacc[NQT][DB];
+    float m_run[NQT], l_run[NQT];
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+        m_run[t] = -INFINITY;
+        l_run[t] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
+    }
+
+    unsigned char* slab = lds + wave * SLAB;
+    // V slab write position of this lane: coalesced rows, 16 bytes per lane
+    constexpr int LPR = D / 8;             // lanes per key row
+    constexpr int RPI = kWave / LPR;       // key rows per load instruction
+    constexpr int NVL = kTile / RPI;       // load instructions per V tile
+    const int v_row = lane / LPR, v_chunk = lane % LPR;
+    // transposing-read address of this lane inside the slab: 16-lane blocks cover 4 keys x 16 d
+    const int blk = lane >> 4, i16 = lane & 15;
+    const int tr_off = ((blk >> 1) * 4 + (i16 >> 2)) * VSTRIDE + ((blk & 1) * 16 + (i16 & 3) * 4) * 2;
+
+    for (int tile = t_lo + wave; tile < t_hi; tile += kAttnWaves) {
+        const int kbase = tile * kTile;
+        // K fragments straight from global memory (A operand: lane = key row ln, 8 contiguous d)
+        bf16x8 kf[KS];
+        {
+            int key = kbase + ln;
+            key = key < seg_len ? key : seg_len - 1;
+            const __bf16* kp = Kseg + (long long)key * stride_t;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kf[s] = load_bf16x8(kp + (2 * s + hh) * 8);
+        }
+        // V tile -> LDS slab (row-major, padded)
+        {
+            uint4 vr[NVL];
+#pragma unroll
+            for (int i = 0; i < NVL; ++i) {
+                int key = kbase + i * RPI + v_row;
+                key = key < seg_len ? key : seg_len - 1;
+                vr[i] = *reinterpret_cast<const uint4*>(Vseg + (long long)key * stride_t + v_chunk * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < NVL; ++i)
+                *reinterpret_cast<uint4*>(slab + (i * RPI + v_row) * VSTRIDE + v_chunk * 16) = vr[i];
+        }
+
+        bf16x8 pf[NQT][2];
+#pragma unroll
+        for (int t = 0; t < NQT; ++t) {
+            // S^T[key][query] = sum_d K[key][d] Q[query][d]
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[t][s], acc, 0, 0, 0);
+            // register i of this lane is key kbase + (i/4)*8 + hh*4 + i%4 for query row ln
+            const int vis = min(lim[t], seg_len) - kbase - hh * 4;  // key offsets below this are visible
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int koff = (i >> 2) * 8 + (i & 3);
+                float s = acc[i] * prm.scale_log2;
+                s = koff < vis ? s : -INFINITY;
+                acc[i] = s;
+                mx = fmaxf(mx, s);
+            }
+            mx = fmaxf(mx, shfl_xor_f(mx, 32));
+            const float m_new = fmaxf(m_run[t], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = __builtin_amdgcn_exp2f(acc[i] - m_use);
+                psum += pv;
+                pf[t][i >> 3][i & 7] = (__bf16)pv;
+            }
+            l_run[t] = l_run[t] * alpha + psum;
+            m_run[t] = m_new;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[t][db][i] *= alpha;
+        }
+        // O^T[d][query] += sum_key V[key][d] P^T[key][query]; V^T fragments by transposing LDS reads
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const unsigned char* ap = slab + tr_off + (kb * 16) * VSTRIDE + db * 64;
+                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) short4v*)(ap));
+                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) short4v*)(ap + 8 * VSTRIDE));
+                union {
+                    short4v s[2];
+                    bf16x8 v;
+                } vf;
+                vf.s[0] = lo;
+                vf.s[1] = hi;
+#pragma unroll
+                for (int t = 0; t < NQT; ++t)
+                    oacc[t][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[t][kb], oacc[t][db], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- merge the 4 wavefronts' states in a fixed order, then store the item's partial ----
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+        l_run[t] += shfl_xor_f(l_run[t], 32);
+        if (hh == 0) {
+            sh_m[wave][t * kRowTile + ln] = m_run[t];
+            sh_l[wave][t * kRowTile + ln] = l_run[t];
+        }
+    }
+    __syncthreads();  // also: every wavefront is done with its V slab
+    float* obuf = reinterpret_cast<float*>(lds);
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+        float mg = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) mg = fmaxf(mg, sh_m[w][t * kRowTile + ln]);
+        const float mg_use = (mg == -INFINITY) ? 0.f : mg;
+        const float wscale = __builtin_amdgcn_exp2f(m_run[t] - mg_use);
+        for (int w = 0; w < kAttnWaves; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        float4* dst = reinterpret_cast<float4*>(obuf + ln * OSTRIDE + db * 32 + q4 * 8 + hh * 4);
+                        float4 v = make_float4(oacc[t][db][q4 * 4 + 0] * wscale, oacc[t][db][q4 * 4 + 1] * wscale,
+                                               oacc[t][db][q4 * 4 + 2] * wscale, oacc[t][db][q4 * 4 + 3] * wscale);
+                        if (w > 0) {
+                            const float4 o = *dst;
+                            v.x += o.x;
+                            v.y += o.y;
+                            v.z += o.z;
+                            v.w += o.w;
+                        }
+                        *dst = v;
+                    }
+            }
+            __syncthreads();
+        }
+        // cooperative store of the valid rows of this row tile
+        const int nrows = min(kRowTile, rho_end - (rho0 + t * kRowTile));
+        constexpr int F4 = D / 4;
+        for (int e = tid; e < nrows * F4; e += kAttnThreads) {
+            const int row = e / F4, c4 = e - row * F4;
+            const long long rho = rho0 + t * kRowTile + row;
+            const float4 v = *reinterpret_cast<const float4*>(obuf + row * OSTRIDE + c4 * 4);
+            float4* dst = reinterpret_cast<float4*>(
+                prm.part_o + (((long long)kvh * prm.B * GR + rho) * pl.nslots + slot) * D + c4 * 4);
+            *dst = v;
+        }
+        if (tid < nrows) {
+            const int col = t * kRowTile + tid;
+            float mrow = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kAttnWaves; ++w) mrow = fmaxf(mrow, sh_m[w][col]);
+            const float mrow_use = (mrow == -INFINITY) ? 0.f : mrow;
+            float lrow = 0.f;
+#pragma unroll
+            for (int w = 0; w < kAttnWaves; ++w) lrow += sh_l[w][col] * __builtin_amdgcn_exp2f(sh_m[w][col] - mrow_use);
+            const long long rho = rho0 + t * kRowTile + tid;
+            float2* dst = reinterpret_cast<float2*>(prm.part_ml + (((long long)kvh * prm.B * GR + rho) * pl.nslots + slot) * 2);
+            *dst = make_float2(mrow, lrow);
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// merge of the partials of one output row: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams prm) {
+    constexpr int TPR = D / 4;          // threads per output row, 4 floats each
+    constexpr int RPB = 256 / TPR;      // rows per block
+    const int tid = threadIdx.x;
+    const long long row = (long long)blockIdx.x * RPB + tid / TPR;
+    const int c4 = tid % TPR;
+    const long long nrows = (long long)prm.B * prm.R * prm.Hq;
+    if (row >= nrows) return;
+    const int h = (int)(row % prm.Hq);
+    const long long br = row / prm.Hq;
+    const int r = (int)(br % prm.R), b = (int)(br / prm.R);
+    const int kvh = h / prm.G, hg = h - kvh * prm.G;
+    const long long rho = (long long)b * prm.GR + r * prm.G + hg;
+    const int ns = prm.plan.nslots;
+    const long long base = ((long long)kvh * prm.B * prm.GR + rho) * ns;
+    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + base;
+    float M = -INFINITY;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[s].x);
+    float Lsum = 0.f;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < ns; ++s) {
+        const float2 v = ml[s];
+        const float w = __builtin_amdgcn_exp2f(v.x - M);   // a row always sees itself: M is finite
+        Lsum += v.y * w;
+        const float4 po = *reinterpret_cast<const float4*>(prm.part_o + (base + s) * D + c4 * 4);
+        o.x += po.x * w;
+        o.y += po.y * w;
+        o.z += po.z * w;
+        o.w += po.w * w;
+    }
+    const float inv = 1.0f / Lsum;
+    __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
+                 (long long)h * prm.o_stride_h + c4 * 4;
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    bf16x4 ov;
+    ov[0] = (__bf16)(o.x * inv);
+    ov[1] = (__bf16)(o.y * inv);
+    ov[2] = (__bf16)(o.z * inv);
+    ov[3] = (__bf16)(o.w * inv);
+    *reinterpret_cast<bf16x4*>(op) = ov;
+    if (prm.lse && c4 == 0) prm.lse[row] = (M + log2f(Lsum)) * 0.69314718055994530942f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 path: one workgroup per output row, fp32 arithmetic throughout (no matrix cores).
+// Wavefront w takes keys w, w+4, ...; lanes split the head dimension; flash-style running state
+// per wavefront, merged through LDS.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kAttnThreads) void attn_f32_kernel(const AttnParams prm) {
+    constexpr int EPL = D / kWave;  // head-dim elements per lane
+    __shared__ float sh_acc[kAttnWaves][D];
+    __shared__ float sh_ml[kAttnWaves][2];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const long long row = blockIdx.x;
+    const int h = (int)(row % prm.Hq);
+    const long long br = row / prm.Hq;
+    const int r = (int)(br % prm.R), b = (int)(br / prm.R);
+    const int kvh = h / prm.G;
+    int L = prm.priv_len[b];
+    L = L < prm.R ? prm.R : (L > prm.Lmax ? prm.Lmax : L);
+    const int n_priv = L - prm.k + r;
+    const int n = prm.P + n_priv;
+    const float scale = prm.scale_log2 * 0.69314718055994530942f;  // back to the natural-log scale
+    const float* qp = (const float*)prm.Q + (long long)b * prm.q_stride_b + (long long)r * prm.q_stride_r +
+                      (long long)h * prm.q_stride_h;
+    float qv[EPL], acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        qv[e] = qp[lane + e * kWave];
+        acc[e] = 0.f;
+    }
+    float m = -INFINITY, l = 0.f;
+    for (int j = wave; j < n; j += kAttnWaves) {
+        const float *kp, *vp;
+        if (j < prm.P) {
+            const long long off = (long long)kvh * prm.kpre_stride_h + (long long)j * prm.kpre_stride_t;
+            kp = (const float*)prm.Kpre + off;
+            vp = (const float*)prm.Vpre + off;
+        } else {
+            const long long off = (long long)b * prm.kpriv_stride_b + (long long)kvh * prm.kpriv_stride_h +
+                                  (long long)(j - prm.P) * prm.kpriv_stride_t;
+            kp = (const float*)prm.Kpriv + off;
+            vp = (const float*)prm.Vpriv + off;
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s += qv[e] * kp[lane + e * kWave];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += shfl_xor_f(s, d);
+        s *= scale;
+        const float m_new = fmaxf(m, s);
+        const float alpha = expf(m - m_new);
+        const float pv = expf(s - m_new);
+        l = l * alpha + pv;
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * alpha + pv * vp[lane + e * kWave];
+    }
+    if (lane == 0) {
+        sh_ml[wave][0] = m;
+        sh_ml[wave][1] = l;
+    }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) sh_acc[wave][lane + e * kWave] = acc[e];
+    __syncthreads();
+    if (tid < D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, sh_ml[w][0]);
+        float Lsum = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) {
+            const float wgt = (sh_ml[w][0] == -INFINITY) ? 0.f : expf(sh_ml[w][0] - M);
+            Lsum += sh_ml[w][1] * wgt;
+            o += sh_acc[w][tid] * wgt;
+        }
+        float* op = (float*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
+                    (long long)h * prm.o_stride_h;
+        op[tid] = o / Lsum;
+        if (prm.lse && tid == 0) prm.lse[row] = M + logf(Lsum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static int fill_desc(const lotts_attn_desc* in, lotts_attn_desc* d) {
+    if (!in) return LOTTS_ERR_NULL;
+    *d = *in;
+    if (d->dtype != LOTTS_F32 && d->dtype != LOTTS_BF16) return LOTTS_ERR_DTYPE;
+    if (d->B < 1 || d->k < 0 || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0) return LOTTS_ERR_SHAPE;
+    if (d->D != 64 && d->D != 128) return LOTTS_ERR_SHAPE;
+    if (d->P < 0 || d->Lmax < d->k + 1) return LOTTS_ERR_SHAPE;
+    if (!(d->scale >= 0.0f) || d->scale > 3.0e38f) return LOTTS_ERR_SHAPE;
+    const long long R = d->k + 1, D = d->D;
+    // 0 selects the dense layout
+    if (!d->q_stride_h) d->q_stride_h = D;
+    if (!d->q_stride_r) d->q_stride_r = (long long)d->Hq * D;
+    if (!d->q_stride_b) d->q_stride_b = R * d->Hq * D;
+    if (!d->o_stride_h) d->o_stride_h = D;
+    if (!d->o_stride_r) d->o_stride_r = (long long)d->Hq * D;
+    if (!d->o_stride_b) d->o_stride_b = R * d->Hq * D;
+    if (!d->kpre_stride_t) d->kpre_stride_t = D;
+    if (!d->kpre_stride_h) d->kpre_stride_h = (long long)d->P * D;
+    if (!d->kpriv_stride_t) d->kpriv_stride_t = D;
+    if (!d->kpriv_stride_h) d->kpriv_stride_h = (long long)d->Lmax * D;
+    if (!d->kpriv_stride_b) d->kpriv_stride_b = (long long)d->Hkv * d->Lmax * D;
+    const long long st[] = {d->q_stride_b, d->q_stride_r, d->q_stride_h, d->kpre_stride_h, d->kpre_stride_t,
+                            d->kpriv_stride_b, d->kpriv_stride_h, d->kpriv_stride_t, d->o_stride_b, d->o_stride_r,
+                            d->o_stride_h};
+    for (long long s : st) {
+        if (s < 0) return LOTTS_ERR_SHAPE;
+        if (d->dtype == LOTTS_BF16 && (s % 8) != 0) return LOTTS_ERR_SHAPE;  // 16-byte vector loads
+    }
+    if (d->q_stride_h < D || d->o_stride_h < D || d->kpre_stride_t < D || d->kpriv_stride_t < D) return LOTTS_ERR_SHAPE;
+    const long long rows = (long long)d->B * R * d->Hq;
+    if (rows > 0x7fffffffLL / 8) return LOTTS_ERR_SHAPE;
+    return LOTTS_OK;
+}
+
+}  // namespace lotts
+
+extern "C" size_t verify_attention_workspace_bytes(const lotts_attn_desc* desc) {
+    using namespace lotts;
+    lotts_attn_desc d;
+    if (fill_desc(desc, &d) != LOTTS_OK) return 0;
+    if (d.dtype == LOTTS_F32) return 256;  // the fp32 path needs none; keep the pointer non-NULL
+    const AttnPlan pl = plan_attention(d);
+    size_t bytes = part_o_elems(d, pl) * sizeof(float);
+    bytes = (bytes + 255) & ~(size_t)255;
+    bytes += part_ml_elems(d, pl) * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, const void* Kpre, const void* Vpre,
+                                const void* Kpriv, const void* Vpriv, const int32_t* priv_len, void* O, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lotts;
+    lotts_attn_desc d;
+    int rc = fill_desc(desc, &d);
+    if (rc != LOTTS_OK) return rc;
+    if (!Q || !Kpriv || !Vpriv || !priv_len || !O || !workspace) return LOTTS_ERR_NULL;
+    if (d.P > 0 && (!Kpre || !Vpre)) return LOTTS_ERR_NULL;
+    if (workspace_bytes < verify_attention_workspace_bytes(desc)) return LOTTS_ERR_WORKSPACE;
+    const uintptr_t align_or = (uintptr_t)Q | (uintptr_t)Kpre | (uintptr_t)Vpre | (uintptr_t)Kpriv | (uintptr_t)Vpriv |
+                               (uintptr_t)O | (uintptr_t)workspace;
+    if (d.dtype == LOTTS_BF16 && (align_or & 15) != 0) return LOTTS_ERR_SHAPE;
+    if ((align_or & 3) != 0) return LOTTS_ERR_SHAPE;
+
+    AttnParams prm;
+    prm.Q = Q; prm.Kpre = Kpre; prm.Vpre = Vpre; prm.Kpriv = Kpriv; prm.Vpriv = Vpriv;
+    prm.priv_len = priv_len;
+    prm.O = O; prm.lse = lse;
+    prm.B = d.B; prm.k = d.k; prm.R = d.k + 1; prm.Hq = d.Hq; prm.Hkv = d.Hkv; prm.G = d.Hq / d.Hkv;
+    prm.GR = prm.G * prm.R; prm.D = d.D; prm.P = d.P; prm.Lmax = d.Lmax;
+    const double scale = d.scale > 0.0f ? (double)d.scale : 1.0 / sqrt((double)d.D);
+    prm.scale_log2 = (float)(scale * 1.4426950408889634074);
+    prm.q_stride_b = d.q_stride_b; prm.q_stride_r = d.q_stride_r; prm.q_stride_h = d.q_stride_h;
+    prm.kpre_stride_h = d.kpre_stride_h; prm.kpre_stride_t = d.kpre_stride_t;
+    prm.kpriv_stride_b = d.kpriv_stride_b; prm.kpriv_stride_h = d.kpriv_stride_h; prm.kpriv_stride_t = d.kpriv_stride_t;
+    prm.o_stride_b = d.o_stride_b; prm.o_stride_r = d.o_stride_r; prm.o_stride_h = d.o_stride_h;
+    hipStream_t s = (hipStream_t)stream;
+    const long long rows = (long long)d.B * prm.R * d.Hq;
+
+    if (d.dtype == LOTTS_F32) {
+        prm.plan = AttnPlan{};
+        prm.part_o = nullptr; prm.part_ml = nullptr;
+        if (d.D == 64)
+            hipLaunchKernelGGL(attn_f32_kernel<64>, dim3((unsigned)rows), dim3(kAttnThreads), 0, s, prm);
+        else
+            hipLaunchKernelGGL(attn_f32_kernel<128>, dim3((unsigned)rows), dim3(kAttnThreads), 0, s, prm);
+        return check_launch();
+    }
+
+    prm.plan = plan_attention(d);
+    const AttnPlan& pl = prm.plan;
+    prm.part_o = static_cast<float*>(workspace);
+    size_t off = part_o_elems(d, pl) * sizeof(float);
+    off = (off + 255) & ~(size_t)255;
+    prm.part_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off);
+    const long long items = (long long)pl.n_pre_items + pl.n_priv_items;
+    if (items > 0x7fffffffLL) return LOTTS_ERR_SHAPE;
+    const dim3 grid((unsigned)items), block(kAttnThreads);
+    if (d.D == 128 && pl.nqt == 1) hipLaunchKernelGGL((attn_partial_kernel<128, 1>), grid, block, 0, s, prm);
+    else if (d.D == 128) hipLaunchKernelGGL((attn_partial_kernel<128, 2>), grid, block, 0, s, prm);
+    else if (pl.nqt == 1) hipLaunchKernelGGL((attn_partial_kernel<64, 1>), grid, block, 0, s, prm);
+    else hipLaunchKernelGGL((attn_partial_kernel<64, 2>), grid, block, 0, s, prm);
+    rc = check_launch();
+    if (rc != LOTTS_OK) return rc;
+    if (d.D == 128) {
+        const int rpb = 256 / (128 / 4);
+        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, s, prm);
+    } else {
+        const int rpb = 256 / (64 / 4);
+        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, s, prm);
+    }
+    return check_launch();
+}

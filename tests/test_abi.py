@@ -1,0 +1,97 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects malformed calls before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2505_19634_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_19634_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lotts.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2505_19634_amd import binding
+    syms = declared_symbols()
+    assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def test_strerror(lib):
+    from paper_2505_19634_amd import binding
+    assert binding.strerror(0) == "ok"
+    for code in range(-5, 0):
+        assert binding.strerror(code) not in ("ok", "unknown lotts status")
+    assert binding.strerror(-99) == "unknown lotts status"
+
+
+def make_desc(**kw):
+    from paper_2505_19634_amd.binding import AttnDesc
+    d = AttnDesc()
+    base = dict(B=16, k=3, Hq=40, Hkv=8, D=128, P=256, Lmax=3840, dtype=1, scale=0.0)
+    base.update(kw)
+    for n, v in base.items():
+        setattr(d, n, v)
+    return d
+
+
+def test_workspace_queries(lib):
+    d = make_desc()
+    need = lib.verify_attention_workspace_bytes(ctypes.byref(d))
+    assert 0 < need < 64 << 20 and need % 256 == 0
+    for bad in (dict(Hq=41), dict(D=96), dict(k=-1), dict(B=0), dict(Lmax=3), dict(dtype=7), dict(P=-1),
+                dict(q_stride_h=12)):
+        assert lib.verify_attention_workspace_bytes(ctypes.byref(make_desc(**bad))) == 0, bad
+    assert lib.verify_attention_workspace_bytes(None) == 0
+    assert lib.spec_accept_workspace_bytes(16, 3, 152064) > 0
+    assert lib.spec_accept_workspace_bytes(0, 3, 100) == 0
+    assert lib.spec_accept_workspace_bytes(4, -1, 100) == 0
+    assert lib.spec_accept_workspace_bytes(4, 3, 0) == 0
+
+
+def test_calls_are_rejected_before_any_launch(lib):
+    """Only error paths: each returns on the host, so this is safe without a GPU."""
+    d = make_desc()
+    one = ctypes.c_void_p(4096)        # never dereferenced: a different check fails first
+    assert lib.verify_attention(None, one, one, one, one, one, one, one, None, one, 1 << 30, None) == -1
+    assert lib.verify_attention(ctypes.byref(d), None, one, one, one, one, one, one, None, one, 1 << 30, None) == -1
+    assert lib.verify_attention(ctypes.byref(d), one, None, one, one, one, one, one, None, one, 1 << 30, None) == -1
+    assert lib.verify_attention(ctypes.byref(d), one, one, one, one, one, one, one, None, one, 16, None) == -4
+    assert lib.verify_attention(ctypes.byref(make_desc(Hq=41)), one, one, one, one, one, one, one, None, one,
+                                1 << 30, None) == -2
+    assert lib.verify_attention(ctypes.byref(make_desc(dtype=5)), one, one, one, one, one, one, one, None, one,
+                                1 << 30, None) == -3
+    odd = ctypes.c_void_p(4096 + 2)    # bf16 rows must be 16-byte aligned
+    assert lib.verify_attention(ctypes.byref(d), odd, one, one, one, one, one, one, None, one, 1 << 30, None) == -2
+    assert lib.spec_accept(4, 2, 100, None, one, one, one, one, one, one, 1 << 20, None) == -1
+    assert lib.spec_accept(4, 2, 100, one, None, one, one, one, one, one, 1 << 20, None) == -1
+    assert lib.spec_accept(4, 2, 100, one, one, one, one, one, one, one, 8, None) == -4
+    assert lib.spec_accept(4, 300, 100, one, one, one, one, one, one, one, 1 << 20, None) == -2
+    assert lib.spec_accept(0, 2, 100, one, one, one, one, one, one, one, 1 << 20, None) == -2
+    assert lib.majority_vote(1, 16, None, one, one, None) == -1
+    assert lib.majority_vote(1, 0, one, one, one, None) == -2
+    assert lib.majority_vote(1, 5000, one, one, one, None) == -2
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    import paper_2505_19634_amd as lotts
+    with pytest.raises(ValueError):
+        lotts.majority_vote(torch.zeros(4, dtype=torch.int32))
+    with pytest.raises(ValueError):
+        lotts.spec_accept(torch.zeros(1, 1, 8), None, None, torch.zeros(1, 1))

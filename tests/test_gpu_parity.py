@@ -1,0 +1,221 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the CPU
+oracle on the same seeded inputs.  Indices must match bit for bit; attention must stay within
+2e-2 max-abs and 1e-2 Frobenius-relative of the fp64 oracle for bf16 (1e-4 / 1e-4 for fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from gpu_util import DEV, TOL, attn_errors, attn_to_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lotts():
+    import paper_2505_19634_amd as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def run_attention(lotts, oracle, cfg, priv_len=None, Lmax=None, scale=0.0):
+    a = S.attention_inputs(cfg, priv_len=priv_len, Lmax=Lmax)
+    d = attn_to_dev(cfg, a)
+    print("attention case", cfg, "priv_len", None if priv_len is None else list(priv_len), flush=True)
+    O, lse = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"],
+                                    scale=scale, return_lse=True)
+    torch.cuda.synchronize()
+    Oref, lref = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"],
+                                         scale=scale)
+    e_abs, e_fro, e_rel = attn_errors(O, Oref)
+    tol = TOL[cfg.dtype]
+    print("  max-abs %.3g  fro-rel %.3g  max-rel(non-tiny) %.3g" % (e_abs, e_fro, e_rel), flush=True)
+    assert e_abs <= tol["abs"] and e_fro <= tol["fro"]
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - lref).max() <= tol["lse"]
+    return O
+
+
+BF = S.CONFIGS["C3"]
+SMALL_ATTN = [
+    S.CONFIGS["C1"],                                                 # tiny fp32, the configs[0] case
+    S.CONFIGS["C1"].with_(B=3, Hq=8, Hkv=2, D=128, P=50, L=77, k=2),  # fp32, GQA, D=128, ragged tiles
+    BF.with_(B=3, P=96, L=200),                                      # several tiles + ragged tail, G*R = 20
+    BF.with_(B=2, P=0, L=131),                                       # no prefix
+    BF.with_(B=5, P=33, L=4, k=3),                                   # private cache = the new tokens only
+    BF.with_(B=2, P=70, L=300, k=0),                                 # k = 0: decode attention
+    BF.with_(B=3, Hq=16, Hkv=2, k=4, P=64, L=257),                   # G*R = 40: two row tiles
+    BF.with_(B=2, Hq=40, Hkv=8, k=8, P=40, L=190),                   # G*R = 45
+    BF.with_(B=2, Hq=32, Hkv=2, k=4, P=64, L=140),                   # G*R = 80: more than one row group
+    BF.with_(B=4, Hq=8, Hkv=4, D=64, P=100, L=333, k=3),             # head_dim 64
+    BF.with_(B=2, Hq=12, Hkv=2, D=64, k=6, P=31, L=95),              # head_dim 64, two row tiles
+    BF.with_(B=37, Hq=4, Hkv=4, k=1, P=300, L=65),                   # many branches stacked on the prefix
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_ATTN, ids=lambda c: "B%d_k%d_H%d-%d_D%d_P%d_L%d_%s" % (
+    c.B, c.k, c.Hq, c.Hkv, c.D, c.P, c.L, c.dtype))
+def test_attention_small(lotts, oracle, cfg):
+    run_attention(lotts, oracle, cfg)
+
+
+def test_attention_ragged_private_lengths(lotts, oracle):
+    cfg = BF.with_(B=6, P=128, L=700)
+    pl = np.array([700, 4, 5, 333, 32, 699], dtype=np.int32)
+    run_attention(lotts, oracle, cfg, priv_len=pl)
+    run_attention(lotts, oracle, cfg.with_(dtype="f32", Hq=8, Hkv=8, D=64, L=90, P=20),
+                  priv_len=np.array([90, 4, 5, 33, 32, 89], dtype=np.int32))
+
+
+def test_attention_explicit_scale(lotts, oracle):
+    run_attention(lotts, oracle, BF.with_(B=2, P=64, L=100), scale=0.2)
+
+
+def test_attention_token_major_layout(lotts, oracle):
+    """K/V stored [B][L][Hkv][D] (token-major) reach the kernel through the strides."""
+    cfg = BF.with_(B=3, P=96, L=200)
+    a = S.attention_inputs(cfg)
+    d = attn_to_dev(cfg, a)
+    kp = d["Kpriv"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    vp = d["Vpriv"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    kpre = d["Kpre"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    vpre = d["Vpre"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    assert not kp.is_contiguous()
+    O = lotts.verify_attention(d["Q"], kpre, vpre, kp, vp, d["priv_len"])
+    O2 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    assert torch.equal(O, O2)            # same arithmetic, only the addresses differ
+    Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
+    e_abs, e_fro, _ = attn_errors(O, Oref)
+    assert e_abs <= 2e-2 and e_fro <= 1e-2
+
+
+def test_attention_is_deterministic(lotts):
+    cfg = BF.with_(B=4, P=128, L=900)
+    d = attn_to_dev(cfg, S.attention_inputs(cfg))
+    O1 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"]).clone()
+    O2 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    assert torch.equal(O1, O2)
+
+
+def test_attention_ignores_what_rows_cannot_see(lotts):
+    """NaNs in later drafts' K/V rows and beyond priv_len must not reach earlier rows."""
+    cfg = BF.with_(B=2, P=64, L=150)
+    a = S.attention_inputs(cfg, priv_len=np.array([150, 100], np.int32))
+    d = attn_to_dev(cfg, a)
+    O1 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"]).clone()
+    d["Kpriv"][1, :, 100:] = float("nan")          # beyond the branch's length
+    d["Vpriv"][1, :, 100:] = float("nan")
+    d["Kpriv"][0, :, 149] = float("inf")           # the last draft's own K/V: only row k may see it
+    O2 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    assert torch.equal(O1[1], O2[1])
+    assert torch.equal(O1[0, :cfg.k], O2[0, :cfg.k])
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C5"])
+def test_attention_full_size(lotts, oracle, name):
+    """The paper-shaped workloads at full size, in the launch configuration bench.py times."""
+    run_attention(lotts, oracle, S.CONFIGS[name])
+
+
+@pytest.mark.parametrize("B", [1, 4, 16])
+def test_attention_branch_sweep(lotts, oracle, B):
+    run_attention(lotts, oracle, S.CONFIGS["C4"].with_(B=B))
+
+
+# ---------------------------------------------------------------------------- acceptance
+def run_accept(lotts, oracle, s):
+    p, q, draft, u = s["p"], s["q"], s["draft"], s["u"]
+    k = p.shape[1] - 1
+    n, t = lotts.spec_accept(to_dev(p), to_dev(q) if k else None, to_dev(draft) if k else None, to_dev(u))
+    torch.cuda.synchronize()
+    n_ref, t_ref = oracle.spec_accept(p, q, draft, u)
+    assert np.array_equal(n.cpu().numpy(), n_ref), (n.cpu().numpy(), n_ref)
+    assert np.array_equal(t.cpu().numpy(), t_ref), (t.cpu().numpy(), t_ref)
+    return n_ref, t_ref
+
+
+@pytest.mark.parametrize("cfg", [
+    S.CONFIGS["C1"],
+    S.CONFIGS["C1"].with_(B=7, V=999, k=2),            # V not a multiple of 4: scalar loads
+    S.CONFIGS["C1"].with_(B=5, V=2048 * 3 + 1, k=5),   # one element into a fourth chunk
+    S.CONFIGS["C1"].with_(B=9, V=4, k=1),
+    S.CONFIGS["C1"].with_(B=3, V=1, k=2),
+    S.CONFIGS["C1"].with_(B=6, V=5000, k=0),           # k = 0: plain sampling from p_0
+    S.CONFIGS["C2"].with_(B=33, V=20000, k=8),
+    S.CONFIGS["C5"].with_(B=64, V=40000),              # frequent rejection
+], ids=lambda c: "B%d_k%d_V%d" % (c.B, c.k, c.V))
+def test_accept_small(lotts, oracle, cfg):
+    print("accept case", cfg, flush=True)
+    run_accept(lotts, oracle, S.accept_inputs(cfg))
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C5"])
+def test_accept_full_size(lotts, oracle, name):
+    cfg = S.CONFIGS[name]
+    print("accept case", cfg, flush=True)
+    n, _ = run_accept(lotts, oracle, S.accept_inputs(cfg))
+    assert n.min() < cfg.k or cfg.B < 4                # rejections do occur
+
+
+def test_accept_many_uniforms_on_one_row(lotts, oracle):
+    """Sweep the sampling uniform densely over fixed rows: every crossing the oracle finds, the GPU finds."""
+    cfg = S.CONFIGS["C2"].with_(B=1, V=30000, k=2)
+    s = S.accept_inputs(cfg)
+    N = 4096
+    g = np.random.default_rng(5)
+    p = np.ascontiguousarray(np.broadcast_to(s["p"], (N, 3, cfg.V)))
+    q = np.ascontiguousarray(np.broadcast_to(s["q"], (N, 2, cfg.V)))
+    draft = g.integers(0, cfg.V, size=(N, 2)).astype(np.int32)
+    u = (g.integers(0, 1 << 24, size=(N, 3)) / float(1 << 24)).astype(np.float32)
+    u[::5, 2] = 0.0
+    u[1::5, 2] = np.nextafter(np.float32(1), np.float32(0))
+    n, t = run_accept(lotts, oracle, dict(p=p, q=q, draft=draft, u=u))
+    assert len(np.unique(t)) > 1000
+
+
+def test_accept_degenerate_rows(lotts, oracle):
+    V, k = 4096, 2
+    g = np.random.default_rng(9)
+    x = g.random((4, k + 1, V)).astype(np.float32)
+    p = (x / x.sum(-1, keepdims=True)).astype(np.float32)
+    q = p[:, :k].copy()                         # identical: everything is accepted unless p(x) = 0
+    draft = np.array([[5, 6], [7, 8], [9, 10], [11, 12]], np.int32)
+    p[1, 0, 7] = 0.0
+    q[1, 0, 7] = 0.0                            # branch 1: rejected at 0 with an empty residual -> sample p_0
+    p[2] = 0.0
+    q[2] = 0.0                                  # branch 2: no mass anywhere -> -1
+    p[3, 1, :] = 0.0
+    p[3, 1, 100] = 1.0                          # branch 3: one-hot target at position 1, draft 12 rejected
+    u = np.array([[0.3, 0.4, 0.5]] * 4, np.float32)
+    n, t = run_accept(lotts, oracle, dict(p=p, q=q, draft=draft, u=u))
+    assert list(n) == [2, 0, 0, 1] and t[2] == -1 and t[3] == 100
+
+
+def test_accept_is_deterministic(lotts):
+    cfg = S.CONFIGS["C3"].with_(B=8, V=50000)
+    s = S.accept_inputs(cfg)
+    d = [to_dev(s[x]) for x in ("p", "q", "draft", "u")]
+    n1, t1 = lotts.spec_accept(*d)
+    n1, t1 = n1.clone(), t1.clone()
+    n2, t2 = lotts.spec_accept(*d)
+    assert torch.equal(n1, n2) and torch.equal(t1, t2)
+
+
+# ---------------------------------------------------------------------------- vote
+@pytest.mark.parametrize("N,B", [(1, 16), (1, 1), (7, 64), (3, 4096), (50, 33)])
+def test_vote(lotts, oracle, N, B):
+    cfg = S.CONFIGS["C3"].with_(B=B)
+    a = S.vote_inputs(cfg, N=N, salt=B)
+    if N > 1:
+        a[1, ::3] = -1
+        a[2, :] = -1
+    w, c = lotts.majority_vote(to_dev(a))
+    w_ref, c_ref = oracle.majority_vote(a)
+    assert np.array_equal(w.cpu().numpy(), w_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+
+
+def test_vote_ties_go_to_first_occurrence(lotts, oracle):
+    a = np.array([[4, 9, 9, 4, 2], [9, 4, 4, 9, 2], [1, 2, 3, 4, 5], [-1, 3, -1, 3, 7]], np.int32)
+    w, c = lotts.majority_vote(to_dev(a))
+    assert w.cpu().tolist() == [4, 9, 1, 3] and c.cpu().tolist() == [2, 2, 1, 2]
+    w_ref, c_ref = oracle.majority_vote(a)
+    assert w.cpu().tolist() == list(w_ref) and c.cpu().tolist() == list(c_ref)
