@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Throughput of the speculative verification step across B branches on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input, all launched on one
+stream: verify_attention (one layer) -> spec_accept -> majority_vote.  Inputs are resident in
+HBM before the timed region; several independent input sets are rotated so that the 256 MB
+memory-side cache cannot serve the KV stream.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--sets 4]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def attn_algorithmic_bytes(cfg, priv_len_sum=None) -> int:
+    """What the method must move per layer: every prefix token once (whatever B is), every private
+    token once, Q in and O out.  2 (K and V) * Hkv * D * element size per token."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    per_token = 2 * cfg.Hkv * cfg.D * es
+    priv = cfg.B * cfg.L if priv_len_sum is None else priv_len_sum
+    return per_token * (cfg.P + priv) + 2 * cfg.B * cfg.R * cfg.Hq * cfg.D * es
+
+
+def accept_algorithmic_bytes(cfg, accept_len) -> int:
+    """One read of the row(s) that are sampled: p_n and q_n after a rejection, p_k otherwise."""
+    return int(sum((2 if n < cfg.k else 1) * cfg.V * 4 for n in accept_len))
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "attn_partial_%s_traffic.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="C3", help="C2, C3, C5 or C4xB (e.g. C4x16)")
+    ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (branches shard trivially, "
+              "see DESIGN.md)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2505_19634_amd as lotts
+    from paper_2505_19634_amd import binding
+    import synth_inputs as S
+
+    if args.workload.startswith("C4x"):
+        cfg = S.CONFIGS["C4"].with_(B=int(args.workload[3:]))
+    else:
+        cfg = S.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = binding.load()
+    bf = cfg.dtype == "bf16"
+    nsets = max(1, args.sets)
+
+    # ---- inputs: set 0 from the host generator (also fed to the oracle), the others drawn on the
+    # GPU from the same distributions (they only have to occupy distinct memory)
+    a0 = S.attention_inputs(cfg)
+    s0 = S.accept_inputs(cfg)
+    answers0 = S.vote_inputs(cfg, N=1)
+
+    def dev_kv(x):
+        t = torch.from_numpy(x).to(dev)
+        return t.view(torch.bfloat16) if bf else t
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1000 * cfg.number)
+    sets = []
+    for i in range(nsets):
+        if i == 0:
+            d = {n: dev_kv(a0[n]) for n in ("Q", "Kpre", "Vpre", "Kpriv", "Vpriv")}
+            d.update({n: torch.from_numpy(s0[n]).to(dev) for n in ("p", "q", "draft", "u")})
+        else:
+            d = {}
+            for n in ("Q", "Kpre", "Vpre", "Kpriv", "Vpriv"):
+                t = torch.randn(a0[n].shape, generator=gen, device=dev, dtype=torch.float32) * cfg.qkv_std
+                d[n] = t.to(torch.bfloat16) if bf else t
+            z = torch.randn(s0["p"].shape, generator=gen, device=dev) * cfg.logit_std
+            zq = z[:, :cfg.k] + torch.randn(s0["q"].shape, generator=gen, device=dev) * (cfg.noise_std or cfg.logit_std)
+            d["p"] = torch.softmax(z.double(), -1).float().contiguous()
+            d["q"] = torch.softmax(zq.double(), -1).float().contiguous()
+            d["draft"] = torch.multinomial(d["q"].view(-1, cfg.V), 1, generator=gen).view(cfg.B, cfg.k).int()
+            d["u"] = (torch.randint(0, 1 << 24, (cfg.B, cfg.R), generator=gen, device=dev).float() / float(1 << 24))
+            del z, zq
+        d["priv_len"] = torch.from_numpy(a0["priv_len"]).to(dev)
+        d["answers"] = torch.from_numpy(answers0).to(dev)
+        d["O"] = torch.empty_like(d["Q"])
+        d["accept_len"] = torch.empty((cfg.B,), dtype=torch.int32, device=dev)
+        d["next_token"] = torch.empty((cfg.B,), dtype=torch.int32, device=dev)
+        d["winner"] = torch.empty((1,), dtype=torch.int32, device=dev)
+        d["winner_count"] = torch.empty((1,), dtype=torch.int32, device=dev)
+        sets.append(d)
+
+    # ---- marshal every call once; the timed loop only issues C-ABI calls
+    stream = torch.cuda.current_stream()
+    sh = ctypes.c_void_p(int(stream.cuda_stream))
+    desc = binding.make_attn_desc(sets[0]["Q"], sets[0]["Kpre"], sets[0]["Kpriv"], sets[0]["O"])
+    ws_attn_bytes = lib.verify_attention_workspace_bytes(ctypes.byref(desc))
+    ws_acc_bytes = lib.spec_accept_workspace_bytes(cfg.B, cfg.k, cfg.V)
+    ws_attn = torch.empty(ws_attn_bytes, dtype=torch.uint8, device=dev)
+    ws_acc = torch.empty(ws_acc_bytes, dtype=torch.uint8, device=dev)
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    calls = []
+    for d in sets:
+        attn_args = (ctypes.byref(desc), P(d["Q"]), P(d["Kpre"]), P(d["Vpre"]), P(d["Kpriv"]), P(d["Vpriv"]),
+                     P(d["priv_len"]), P(d["O"]), None, P(ws_attn), ws_attn_bytes, sh)
+        acc_args = (cfg.B, cfg.k, cfg.V, P(d["p"]), P(d["q"]) if cfg.k else None, P(d["draft"]) if cfg.k else None,
+                    P(d["u"]), P(d["accept_len"]), P(d["next_token"]), P(ws_acc), ws_acc_bytes, sh)
+        vote_args = (1, cfg.B, P(d["answers"]), P(d["winner"]), P(d["winner_count"]), sh)
+        calls.append((attn_args, acc_args, vote_args))
+
+    def step(i, ev=None):
+        attn_args, acc_args, vote_args = calls[i % nsets]
+        if ev is not None:
+            ev[0].record(stream)
+        rc = lib.verify_attention(*attn_args)
+        if ev is not None:
+            ev[1].record(stream)
+        rc |= lib.spec_accept(*acc_args)
+        if ev is not None:
+            ev[2].record(stream)
+        rc |= lib.majority_vote(*vote_args)
+        if ev is not None:
+            ev[3].record(stream)
+        if rc != 0:
+            raise RuntimeError("a lotts call failed (status %d)" % rc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps, sync on both sides; HIP events on the launch stream
+    # split it per entry point
+    K = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / K
+    acc_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K
+    vote_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / K
+
+    # cache-resident variant for comparison: one input set only
+    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(min(K, 100))]
+    for e in ev2:
+        e[0].record(stream)
+        lib.verify_attention(*calls[0][0])
+        e[1].record(stream)
+    torch.cuda.synchronize()
+    attn_ms_resident = sum(e[0].elapsed_time(e[1]) for e in ev2) / len(ev2)
+
+    tokens = cfg.B * cfg.R
+    n0 = sets[0]["accept_len"].cpu().numpy()
+    bytes_attn = attn_algorithmic_bytes(cfg)
+    bytes_acc = accept_algorithmic_bytes(cfg, n0)
+    achieved = bytes_attn / (attn_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "verified branch-tokens/sec per verify step",
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d k=%d Hq=%d Hkv=%d D=%d prefix=%d private=%d V=%d, 1 layer; step = "
+                               "verify_attention + spec_accept + majority_vote" % (
+                                   cfg.name, cfg.B, cfg.k, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, cfg.L, cfg.V),
+                   "input_sets_rotated": nsets},
+        "roofline": {"bound": "hbm", "kernel": "verify_attention (attn_partial_kernel + merge)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                     "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms,
+                     "avg_launch_ms_single_set_cache_resident": attn_ms_resident},
+        "breakdown_ms": {"verify_attention": attn_ms, "spec_accept": acc_ms, "majority_vote": vote_ms},
+        "spec_accept": {"algorithmic_bytes": bytes_acc, "GB/s": bytes_acc / (acc_ms * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": bytes_acc / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "mean_accepted": float(n0.mean()),
+                        "emitted_tokens_per_s": float((n0 + 1).sum()) / (ms_per_step * 1e-3)},
+    }
+
+    # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
+    if not args.no_cpu_baseline:
+        import oracle
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 50:
+            c0 = time.perf_counter()
+            oracle.verify_attention(a0["Q"], a0["Kpre"], a0["Vpre"], a0["Kpriv"], a0["Vpriv"], a0["priv_len"],
+                                    want_lse=False)
+            oracle.spec_accept(s0["p"], s0["q"], s0["draft"], s0["u"])
+            oracle.majority_vote(answers0)
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        out["cpu_baseline"] = {"value": tokens * reps / t_cpu, "unit": "tokens/s", "cores": oracle.n_threads(),
+                               "kind": "oracle",
+                               "sample": "%d full steps of the same workload (input set 0), fp64, OpenMP over "
+                                         "(branch, head)" % reps}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

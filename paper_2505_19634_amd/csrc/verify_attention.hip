@@ -27,6 +27,7 @@ namespace lotts {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
@@ -113,8 +114,10 @@ template <int D, int NQT>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const AttnParams prm) {
     constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide blocks of the head dimension
-    constexpr int VSTRIDE = D * 2 + 64;    // bytes per key row of the V slab (pad: no bank conflicts)
-    constexpr int SLAB = kTile * VSTRIDE;  // bytes of V slab per wavefront
+    constexpr int KSTRIDE = D * 2 + 16;    // bytes per key row of the K slab (pad: conflict-free 16-byte row reads)
+    constexpr int VSTRIDE = D * 2 + 64;    // bytes per key row of the V slab (pad: conflict-free transposing reads)
+    constexpr int KSLAB = kTile * KSTRIDE, VSLAB = kTile * VSTRIDE;
+    constexpr int SLAB = KSLAB + VSLAB;    // bytes of LDS per wavefront
     constexpr int OSTRIDE = D + 4;         // floats per row of the merge buffer
     constexpr int MERGE_BYTES = kRowTile * OSTRIDE * 4;
     constexpr int LDS_MAIN = (kAttnWaves * SLAB > MERGE_BYTES) ? kAttnWaves * SLAB : MERGE_BYTES;
@@ -210,40 +213,48 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
-    unsigned char* slab = lds + wave * SLAB;
-    // V slab write position of this lane: coalesced rows, 16 bytes per lane
+    unsigned char* kslab = lds + wave * SLAB;
+    unsigned char* vslab = kslab + KSLAB;
+    // Tile staging: every load instruction of the wavefront covers RPI whole key rows (16 bytes per
+    // lane, consecutive lanes consecutive addresses), the same pattern for K and V.
     constexpr int LPR = D / 8;             // lanes per key row
     constexpr int RPI = kWave / LPR;       // key rows per load instruction
-    constexpr int NVL = kTile / RPI;       // load instructions per V tile
+    constexpr int NVL = kTile / RPI;       // load instructions per tile and operand
     const int v_row = lane / LPR, v_chunk = lane % LPR;
-    // transposing-read address of this lane inside the slab: 16-lane blocks cover 4 keys x 16 d
+    // transposing-read address of this lane inside the V slab: 16-lane blocks cover 4 keys x 16 d
     const int blk = lane >> 4, i16 = lane & 15;
     const int tr_off = ((blk >> 1) * 4 + (i16 >> 2)) * VSTRIDE + ((blk & 1) * 16 + (i16 & 3) * 4) * 2;
 
-    for (int tile = t_lo + wave; tile < t_hi; tile += kAttnWaves) {
+    // The next tile is fetched into registers while the current one is being consumed from LDS.
+    // K and V are read exactly once, so the loads carry the non-temporal hint.
+    u32x4 kst[NVL], vst[NVL];
+    auto fetch = [&](int tile_) {
+        const int kb_ = tile_ * kTile;
+#pragma unroll
+        for (int i = 0; i < NVL; ++i) {
+            int key = kb_ + i * RPI + v_row;
+            key = key < seg_len ? key : seg_len - 1;  // a ragged last tile re-reads the last row; masked below
+            const long long off = (long long)key * stride_t + v_chunk * 8;
+            kst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kseg + off));
+            vst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vseg + off));
+        }
+    };
+    int tile = t_lo + wave;
+    if (tile < t_hi) fetch(tile);
+
+    for (; tile < t_hi; tile += kAttnWaves) {
         const int kbase = tile * kTile;
-        // K fragments straight from global memory (A operand: lane = key row ln, 8 contiguous d)
+#pragma unroll
+        for (int i = 0; i < NVL; ++i) {
+            *reinterpret_cast<u32x4*>(kslab + (i * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
+            *reinterpret_cast<u32x4*>(vslab + (i * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
+        }
+        if (tile + kAttnWaves < t_hi) fetch(tile + kAttnWaves);
+        // K fragments (A operand of S^T = K Q^T: lane = key row ln, 8 contiguous d)
         bf16x8 kf[KS];
-        {
-            int key = kbase + ln;
-            key = key < seg_len ? key : seg_len - 1;
-            const __bf16* kp = Kseg + (long long)key * stride_t;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) kf[s] = load_bf16x8(kp + (2 * s + hh) * 8);
-        }
-        // V tile -> LDS slab (row-major, padded)
-        {
-            uint4 vr[NVL];
-#pragma unroll
-            for (int i = 0; i < NVL; ++i) {
-                int key = kbase + i * RPI + v_row;
-                key = key < seg_len ? key : seg_len - 1;
-                vr[i] = *reinterpret_cast<const uint4*>(Vseg + (long long)key * stride_t + v_chunk * 8);
-            }
-#pragma unroll
-            for (int i = 0; i < NVL; ++i)
-                *reinterpret_cast<uint4*>(slab + (i * RPI + v_row) * VSTRIDE + v_chunk * 16) = vr[i];
-        }
+        for (int s = 0; s < KS; ++s)
+            kf[s] = *reinterpret_cast<const bf16x8*>(kslab + ln * KSTRIDE + (2 * s + hh) * 16);
 
         bf16x8 pf[NQT][2];
 #pragma unroll
@@ -288,7 +299,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const unsigned char* ap = slab + tr_off + (kb * 16) * VSTRIDE + db * 64;
+                const unsigned char* ap = vslab + tr_off + (kb * 16) * VSTRIDE + db * 64;
                 const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) short4v*)(ap));
                 const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
