@@ -125,7 +125,7 @@ def main() -> int:
     desc = binding.make_attn_desc(sets[0]["Q"], sets[0]["Kpre"], sets[0]["Kpriv"], sets[0]["O"])
     ws_attn_bytes = lib.verify_attention_workspace_bytes(ctypes.byref(desc))
     ws_acc_bytes = lib.spec_accept_workspace_bytes(cfg.B, cfg.k, cfg.V)
-    ws_attn = torch.empty(ws_attn_bytes, dtype=torch.uint8, device=dev)
+    ws_attn = torch.zeros(ws_attn_bytes, dtype=torch.uint8, device=dev)   # arrival counters start at zero
     ws_acc = torch.empty(ws_acc_bytes, dtype=torch.uint8, device=dev)
     P = lambda t: ctypes.c_void_p(t.data_ptr())
     calls = []
@@ -198,7 +198,7 @@ def main() -> int:
                                "verify_attention + spec_accept + majority_vote" % (
                                    cfg.name, cfg.B, cfg.k, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, cfg.L, cfg.V),
                    "input_sets_rotated": nsets},
-        "roofline": {"bound": "hbm", "kernel": "verify_attention (attn_partial_kernel + merge)",
+        "roofline": {"bound": "hbm", "kernel": "attn_kernel (all of verify_attention: one launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
                      "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms,

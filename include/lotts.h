@@ -10,8 +10,12 @@
  *   - Return value: LOTTS_OK or a negative lotts_status.  All argument checks run on the
  *     host before anything is launched; a failed call launches nothing.
  *   - Scratch memory is passed in as `workspace`; the *_workspace_bytes queries say how much.
- *     Its contents need not be initialised and are undefined afterwards.  Calls that share a
- *     workspace must be ordered on one stream.
+ *     Calls that share a workspace must be ordered on one stream.  spec_accept takes any
+ *     contents.  verify_attention keeps arrival counters in the first 64 KiB of its workspace:
+ *     the buffer must be ZERO-FILLED ONCE before its first use (hipMemset or a fill kernel);
+ *     every call that completes leaves the counters zero again, whatever its geometry, so the
+ *     same buffer serves later calls without clearing.  A buffer that was in use by a call
+ *     that did not complete (device reset, failed launch) must be cleared again.
  */
 #ifndef LOTTS_H
 #define LOTTS_H
@@ -45,7 +49,7 @@ const char *lotts_strerror(int status);
  * K and V of the same segment use the same strides.
  */
 typedef struct {
-    int32_t B;        /* concurrent branches (Section 3.2, branch-wise parallelism), >= 1 */
+    int32_t B;        /* concurrent branches (Section 3.2, branch-wise parallelism), >= 1; B * Hkv <= 16384 */
     int32_t k;        /* draft tokens per branch (sequence-wise parallelism), >= 0 */
     int32_t Hq, Hkv;  /* query / KV heads, Hq % Hkv == 0 */
     int32_t D;        /* head dimension: 64 or 128 */
@@ -82,7 +86,7 @@ size_t verify_attention_workspace_bytes(const lotts_attn_desc *desc);
  *            bounds, but the rows of an offending branch are then unspecified.
  *   O      [B][R][Hq][D] dtype, out
  *   lse    [B][R][Hq] fp32, out, may be NULL: natural-log sum of exp of the scaled scores
- *   workspace: >= verify_attention_workspace_bytes(desc), 256-byte aligned
+ *   workspace: >= verify_attention_workspace_bytes(desc), 16-byte aligned, zero-filled before first use
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs are
  * computed in fp32 throughout.
  */
@@ -109,7 +113,7 @@ size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V);
  *   draft [B][k]  int32 draft tokens in [0, V) (the kernel clamps); NULL iff k == 0
  *   u [B][k+1]    fp32  uniforms in [0, 1)
  *   accept_len [B] int32 out, in [0, k];  next_token [B] int32 out, in [0, V) or -1
- *   workspace: >= spec_accept_workspace_bytes(B, k, V), 256-byte aligned
+ *   workspace: >= spec_accept_workspace_bytes(B, k, V), 8-byte aligned, any contents
  */
 int spec_accept(int32_t B, int32_t k, int32_t V, const float *p, const float *q, const int32_t *draft,
                 const float *u, int32_t *accept_len, int32_t *next_token, void *workspace,

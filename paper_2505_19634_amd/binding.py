@@ -82,11 +82,12 @@ _workspaces: Dict[Tuple[str, int], torch.Tensor] = {}
 
 
 def _workspace(kind: str, device: torch.device, nbytes: int) -> torch.Tensor:
-    """One cached scratch tensor per entry point and device, grown on demand."""
+    """One cached scratch tensor per entry point and device, grown on demand.  Allocated zero-filled:
+    verify_attention wants its arrival counters zero at first use and leaves them zero."""
     key = (kind, device.index if device.index is not None else torch.cuda.current_device())
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=device)
         _workspaces[key] = ws
     return ws
 

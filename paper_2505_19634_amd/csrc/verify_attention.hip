@@ -3,31 +3,44 @@
 // Section 3.2: B branches of one question; Section 2: the target model verifies the drafts in
 // one parallel forward; Section 3.1: the step is bound by loading the KV cache).
 //
-// bf16 path (MFMA, gfx950):
-//   attn_partial_kernel   one launch over "work items".  An item is a range of 32-key tiles of
-//       one KV segment (the shared prefix of a KV head, or one branch's private cache) and a
-//       stack of up to 32*NQT query rows that all read those keys:
-//         - private item: the G*R rows (G = Hq/Hkv query heads x R = k+1 positions) of one
-//           branch and KV head;
-//         - prefix item: rows of SEVERAL branches stacked, so a prefix tile is fetched once per
-//           row stack instead of once per branch.
-//       The 4 wavefronts of a workgroup take tiles round-robin; each streams its own K tile
-//       straight into MFMA operand registers and its V tile through a private LDS slab (read
-//       back with the transposing LDS load), keeps flash-style running (max, sum, O) state, and
-//       the 4 states are merged through LDS in a fixed order.  The item's un-normalised
-//       partial goes to the workspace.
-//   attn_merge_kernel     log-sum-exp merge of the prefix and private partials, normalise,
-//       convert, store O (and LSE).
+// bf16 path (MFMA, gfx950), ONE launch:
+//   attn_kernel           one launch over "work items", one 4-wavefront workgroup each.  An item
+//       is a share of the keys of one KV segment and a stack of up to 32*NQT query rows that all
+//       read those keys:
+//         - private item: the G*R rows (G = Hq/Hkv query heads x R = k+1 positions) of one branch
+//           and KV head, against a share of that branch's private keys;
+//         - prefix item ("stacked" plan): rows of SEVERAL branches stacked on the MFMA N dimension
+//           against a share of the shared prefix, so a prefix tile is fetched once per row stack
+//           instead of once per branch;
+//         - "folded" plan (prefix short next to the private caches): there are no prefix items;
+//           each private item first runs its share of the prefix keys for its own rows (served by
+//           the L2 after the first touch, so HBM still sees the prefix once) and continues into
+//           the private keys with the same running state -- no extra partial, no extra workgroups.
+//       Each wavefront streams a contiguous run of keys in 32-key tiles: coalesced non-temporal
+//       16-byte loads into registers one tile ahead, staged through a wavefront-private LDS slab
+//       (K read back row-wise as the MFMA A operand, V with the transposing LDS load), S^T = K Q^T
+//       and O^T += V^T P^T on 32x32x16 bf16 MFMA, flash-style running (max, sum, O).  The 4 states
+//       are combined through LDS after one barrier and the item's un-normalised partial goes to
+//       the workspace.  Arrivals are counted per (KV head, branch) with one device-scope atomic;
+//       the workgroup that delivers the last partial does the log-sum-exp merge of that branch's
+//       rows, normalises, converts and stores O (and LSE).  Partials cross workgroups -- and XCDs,
+//       each with its own L2 -- inside one launch, so they are written and read with 16-byte
+//       buffer accesses that carry the device-scope cache policy (performed at the memory side of
+//       the L2s); nothing is ever flushed or invalidated cache-wide.
 // fp32 path: attn_f32_kernel, plain fp32 VALU arithmetic, one workgroup per output row; it
 // exists for exactness checks on small fp32 problems, not for speed.
+#include <cstdlib>
+
 #include "lotts_common.h"
 
 namespace lotts {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
@@ -37,10 +50,11 @@ constexpr int kMaxSplit = 64;
 
 struct AttnPlan {
     int nqt;            // row tiles per item: 1 or 2
+    int fold;           // 1: private items also run their share of the prefix (no prefix items)
     int n_rg_priv;      // row groups per (branch, KV head)
-    int n_rg_pre;       // row groups per KV head over all branches' stacked rows
+    int n_rg_pre;       // row groups per KV head over all branches' stacked rows (stacked plan)
     int nsplit_priv;    // key splits of a private segment
-    int nsplit_pre;     // key splits of the prefix (0 if P == 0)
+    int nsplit_pre;     // key splits of the prefix (stacked plan; 0 otherwise)
     int nslots;         // partials per output row
     int n_pre_items, n_priv_items;
 };
@@ -48,8 +62,11 @@ struct AttnPlan {
 struct AttnParams {
     const void *Q, *Kpre, *Vpre, *Kpriv, *Vpriv;
     const int32_t* priv_len;
-    float* part_o;   // [Hkv][B*GR][nslots][D]
-    float* part_ml;  // [Hkv][B*GR][nslots][2]  (running max in log2 units, sum)
+    void* ws;                  // workspace base; everything below lives in it
+    unsigned ws_bytes;
+    unsigned off_o, off_ml;    // byte offsets: partial O [Hkv][B*GR][nslots][D] fp32,
+                               //               partial (running max in log2 units, sum) [Hkv][B*GR][nslots][2] fp32
+    int* counters;             // [Hkv][B] arrivals, at the start of the workspace; zero between calls
     void* O;
     float* lse;
     int B, k, R, Hq, Hkv, G, GR, D, P, Lmax;
@@ -64,7 +81,8 @@ struct AttnParams {
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Launch plan.  Depends on the descriptor only (never on device data), so the workspace query
-// and the launch agree.  Target: about two 4-wave workgroups per compute unit.
+// and the launch agree.  The HBM stream runs best with one streaming workgroup per compute
+// unit, so the private caches are cut into just enough key shares to give every CU one item.
 static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
     AttnPlan pl;
     const int GR = (d.Hq / d.Hkv) * (d.k + 1);
@@ -74,12 +92,18 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
     pl.n_rg_pre = ceil_div(d.B * GR, rows_per_item);
     const int tiles_priv = ceil_div(d.Lmax, kTile);
     const long long base = (long long)d.B * d.Hkv * pl.n_rg_priv;
-    long long want = (2LL * kNumCU + base - 1) / base;
+    long long want = (kNumCU + base - 1) / base;
     int max_split = tiles_priv / kAttnWaves;  // at least one tile per wavefront
     if (max_split > kMaxSplit) max_split = kMaxSplit;
     if (max_split < 1) max_split = 1;
     pl.nsplit_priv = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
-    if (d.P > 0) {
+    // A prefix that is short next to the private caches is folded into the private items.
+    pl.fold = (d.P > 0 && (long long)d.P * 4 <= d.Lmax) ? 1 : 0;
+#ifdef LOTTS_TUNING  // development builds only: override the plan from the environment
+    if (const char* e = getenv("LOTTS_FOLD")) pl.fold = (d.P > 0) ? atoi(e) : 0;
+    if (const char* e = getenv("LOTTS_NSPLIT_PRIV")) pl.nsplit_priv = atoi(e);
+#endif
+    if (d.P > 0 && !pl.fold) {
         const int tiles_pre = ceil_div(d.P, kTile);
         const int tiles_per_item = ceil_div(tiles_priv, pl.nsplit_priv);
         int s = (tiles_pre + tiles_per_item / 2) / tiles_per_item;
@@ -87,6 +111,9 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
         if (cap > kMaxSplit) cap = kMaxSplit;
         if (s > cap) s = cap;
         pl.nsplit_pre = s < 1 ? 1 : s;
+#ifdef LOTTS_TUNING
+        if (const char* e = getenv("LOTTS_NSPLIT_PRE")) pl.nsplit_pre = atoi(e);
+#endif
     } else {
         pl.nsplit_pre = 0;
     }
@@ -103,27 +130,128 @@ static inline size_t part_ml_elems(const lotts_attn_desc& d, const AttnPlan& pl)
     return (size_t)d.Hkv * d.B * (d.Hq / d.Hkv) * (d.k + 1) * pl.nslots * 2;
 }
 
+// Workspace: [arrival counters][partial O][partial (max, sum)], each part 256-byte aligned.  The
+// counter block has the same place and size for every geometry, so a buffer whose counters are zero
+// stays usable when the geometry changes: partials of one call never land where another counts.
+constexpr int kMaxCounters = 16384;
+static inline size_t workspace_layout(const lotts_attn_desc& d, const AttnPlan& pl, size_t* off_o, size_t* off_ml) {
+    size_t bytes = (size_t)kMaxCounters * sizeof(int);
+    if (off_o) *off_o = bytes;
+    bytes += part_o_elems(d, pl) * sizeof(float);
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (off_ml) *off_ml = bytes;
+    bytes += part_ml_elems(d, pl) * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+// 16- and 8-byte accesses to the workspace with the device-scope cache policy (sc0 sc1).
+constexpr int kDevScope = 17;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ws_rsrc(const AttnParams& prm) {
+    return __builtin_amdgcn_make_buffer_rsrc(prm.ws, 0, (int)prm.ws_bytes, 0x00020000);
+}
+__device__ __forceinline__ void ws_store4(__amdgpu_buffer_rsrc_t r, unsigned byte_off, float4 v) {
+    u32x4 u;
+    u[0] = __float_as_uint(v.x); u[1] = __float_as_uint(v.y); u[2] = __float_as_uint(v.z); u[3] = __float_as_uint(v.w);
+    __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, kDevScope);
+}
+__device__ __forceinline__ void ws_store2(__amdgpu_buffer_rsrc_t r, unsigned byte_off, float2 v) {
+    u32x2 u;
+    u[0] = __float_as_uint(v.x); u[1] = __float_as_uint(v.y);
+    __builtin_amdgcn_raw_buffer_store_b64(u, r, (int)byte_off, 0, kDevScope);
+}
+__device__ __forceinline__ float4 ws_load4(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+    const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kDevScope);
+    return make_float4(__uint_as_float(u[0]), __uint_as_float(u[1]), __uint_as_float(u[2]), __uint_as_float(u[3]));
+}
+__device__ __forceinline__ float2 ws_load2(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+    const u32x2 u = __builtin_amdgcn_raw_buffer_load_b64(r, (int)byte_off, 0, kDevScope);
+    return make_float2(__uint_as_float(u[0]), __uint_as_float(u[1]));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Merge of the partials of the G*R output rows of one (KV head, branch), run by the workgroup that
+// delivered the last of them:  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// 4 floats per thread; the partials are taken 4 slots at a time so their loads go out together.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buffer_rsrc_t rs, int kvh, int b, int tid) {
+    constexpr int F4 = D / 4;
+    constexpr int CH = 4;
+    const int ns = prm.plan.nslots;
+    for (int e = tid; e < prm.GR * F4; e += kAttnThreads) {
+        const int rl = e / F4, c4 = e - rl * F4;
+        const int r = rl / prm.G, hg = rl - r * prm.G;
+        const int h = kvh * prm.G + hg;
+        const unsigned base = ((unsigned)kvh * prm.B * prm.GR + (unsigned)b * prm.GR + rl) * ns;
+        float M = -INFINITY, Lsum = 0.f;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < ns; s0 += CH) {
+            float2 mv[CH];
+            float4 pv[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const bool in = s0 + j < ns;
+                mv[j] = in ? ws_load2(rs, prm.off_ml + (base + s0 + j) * 8u) : make_float2(-INFINITY, 0.f);
+                pv[j] = in ? ws_load4(rs, prm.off_o + ((base + s0 + j) * D + c4 * 4) * 4u) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            float Mn = M;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) Mn = fmaxf(Mn, mv[j].x);
+            const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
+            const float a = __builtin_amdgcn_exp2f(M - Mu);
+            Lsum *= a;
+            o.x *= a; o.y *= a; o.z *= a; o.w *= a;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const float w = __builtin_amdgcn_exp2f(mv[j].x - Mu);
+                Lsum += mv[j].y * w;
+                o.x += pv[j].x * w; o.y += pv[j].y * w; o.z += pv[j].z * w; o.w += pv[j].w * w;
+            }
+            M = Mn;
+        }
+        const float inv = 1.0f / Lsum;  // a row always sees itself: Lsum > 0
+        __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
+                     (long long)h * prm.o_stride_h + c4 * 4;
+        bf16x4 ov;
+        ov[0] = (__bf16)(o.x * inv);
+        ov[1] = (__bf16)(o.y * inv);
+        ov[2] = (__bf16)(o.z * inv);
+        ov[3] = (__bf16)(o.w * inv);
+        *reinterpret_cast<bf16x4*>(op) = ov;
+        if (prm.lse && c4 == 0)
+            prm.lse[((long long)b * prm.R + r) * prm.Hq + h] = (M + log2f(Lsum)) * 0.69314718055994530942f;
+    }
+}
+
 __device__ __forceinline__ bf16x8 load_bf16x8(const __bf16* ptr) {
     return *reinterpret_cast<const bf16x8*>(ptr);
 }
+
+// One run of keys a wavefront streams: tiles of 32 keys starting at `lo`, `step` keys apart,
+// keys at or beyond `hi` do not belong to it.
+struct KeyRun {
+    const __bf16 *K, *V;
+    long long stride_t;
+    int lo, hi, step, ntiles;
+};
 
 // ---------------------------------------------------------------------------------------------
 // bf16 partial attention
 // ---------------------------------------------------------------------------------------------
 template <int D, int NQT>
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const AttnParams prm) {
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams prm) {
     constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide blocks of the head dimension
     constexpr int KSTRIDE = D * 2 + 16;    // bytes per key row of the K slab (pad: conflict-free 16-byte row reads)
     constexpr int VSTRIDE = D * 2 + 64;    // bytes per key row of the V slab (pad: conflict-free transposing reads)
     constexpr int KSLAB = kTile * KSTRIDE, VSLAB = kTile * VSTRIDE;
-    constexpr int SLAB = KSLAB + VSLAB;    // bytes of LDS per wavefront
-    constexpr int OSTRIDE = D + 4;         // floats per row of the merge buffer
-    constexpr int MERGE_BYTES = kRowTile * OSTRIDE * 4;
-    constexpr int LDS_MAIN = (kAttnWaves * SLAB > MERGE_BYTES) ? kAttnWaves * SLAB : MERGE_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_MAIN];
-    __shared__ float sh_m[kAttnWaves][kRowTile * NQT];
-    __shared__ float sh_l[kAttnWaves][kRowTile * NQT];
+    constexpr int SLAB = KSLAB + VSLAB;    // bytes of LDS per wavefront while streaming
+    constexpr int OSTRIDE = D + 4;         // floats per row of a wavefront's merge buffer
+    constexpr int OBUF = kRowTile * OSTRIDE * 4;
+    static_assert(OBUF <= SLAB, "the merge buffer reuses the wavefront's slab");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kAttnWaves * SLAB];
+    __shared__ float sh_m[kAttnWaves][kRowTile];
+    __shared__ float sh_l[kAttnWaves][kRowTile];
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31;   // MFMA column (query row) / A row (key or d) owned by this lane
@@ -131,27 +259,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
     const AttnPlan& pl = prm.plan;
     const int GR = prm.GR;
 
-    // ---- decode the work item ----
+    // ---- decode the work item: private items first (one per CU starts at once), prefix items after ----
     int id = blockIdx.x;
+    const bool is_private = id < pl.n_priv_items;
     int kvh, split, nsplit, rho0, rho_end, seg_len, slot, causal_base;
-    const __bf16 *Kseg, *Vseg;
-    long long stride_t;
-    if (id < pl.n_pre_items) {
-        kvh = id % prm.Hkv;
-        int rest = id / prm.Hkv;
-        split = rest % pl.nsplit_pre;
-        const int rg = rest / pl.nsplit_pre;
-        nsplit = pl.nsplit_pre;
-        rho0 = rg * kRowTile * NQT;
-        rho_end = min(prm.B * GR, rho0 + kRowTile * NQT);
-        seg_len = prm.P;
-        causal_base = prm.P;  // every row sees the whole prefix
-        Kseg = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
-        Vseg = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
-        stride_t = prm.kpre_stride_t;
-        slot = split;
-    } else {
-        id -= pl.n_pre_items;
+    KeyRun run[2];   // run[0]: folded prefix share (may be empty), run[1]: the item's own segment
+    run[0].ntiles = 0;
+    if (is_private) {
         kvh = id % prm.Hkv;
         int rest = id / prm.Hkv;
         split = rest % pl.nsplit_priv;
@@ -166,19 +280,86 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
         seg_len = L;
         causal_base = L - prm.k;  // row at position r sees private keys [0, L - k + r)
         const long long off = (long long)b * prm.kpriv_stride_b + (long long)kvh * prm.kpriv_stride_h;
-        Kseg = (const __bf16*)prm.Kpriv + off;
-        Vseg = (const __bf16*)prm.Vpriv + off;
-        stride_t = prm.kpriv_stride_t;
+        run[1].K = (const __bf16*)prm.Kpriv + off;
+        run[1].V = (const __bf16*)prm.Vpriv + off;
+        run[1].stride_t = prm.kpriv_stride_t;
         slot = pl.nsplit_pre + split;
+        if (pl.fold) {
+            // this item's share of the prefix keys (groups of 4), dealt to the wavefronts tile by tile
+            const int pg = (prm.P + 3) >> 2;
+            const int p_lo = (int)((long long)split * pg / nsplit) * 4;
+            const int p_hi = min(prm.P, (int)((long long)(split + 1) * pg / nsplit) * 4);
+            run[0].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
+            run[0].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
+            run[0].stride_t = prm.kpre_stride_t;
+            run[0].lo = p_lo + wave * kTile;
+            run[0].hi = p_hi;
+            run[0].step = kAttnWaves * kTile;
+            run[0].ntiles = run[0].lo < p_hi ? (p_hi - run[0].lo + run[0].step - 1) / run[0].step : 0;
+        }
+    } else {
+        id -= pl.n_priv_items;
+        kvh = id % prm.Hkv;
+        int rest = id / prm.Hkv;
+        split = rest % pl.nsplit_pre;
+        const int rg = rest / pl.nsplit_pre;
+        nsplit = pl.nsplit_pre;
+        rho0 = rg * kRowTile * NQT;
+        rho_end = min(prm.B * GR, rho0 + kRowTile * NQT);
+        seg_len = prm.P;
+        causal_base = prm.P;  // every row sees the whole prefix
+        run[1].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
+        run[1].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
+        run[1].stride_t = prm.kpre_stride_t;
+        slot = split;
     }
-    const bool is_private = blockIdx.x >= pl.n_pre_items;
-    const int ntiles = (seg_len + kTile - 1) / kTile;
-    const int t_lo = (int)((long long)split * ntiles / nsplit);
-    const int t_hi = (int)((long long)(split + 1) * ntiles / nsplit);
+    // Keys of the item's own segment are dealt out in groups of 4 (one load instruction covers whole
+    // groups): the item takes an equal share of the groups and each of its wavefronts an equal,
+    // contiguous share of those, so all wavefronts stream the same number of bytes to within 4 keys.
+    {
+        const int ngroups = (seg_len + 3) >> 2;
+        const int g_lo = (int)((long long)split * ngroups / nsplit);
+        const int g_hi = (int)((long long)(split + 1) * ngroups / nsplit);
+        run[1].lo = (g_lo + (int)((long long)wave * (g_hi - g_lo) / kAttnWaves)) * 4;
+        run[1].hi = min(seg_len, (g_lo + (int)((long long)(wave + 1) * (g_hi - g_lo) / kAttnWaves)) * 4);
+        run[1].step = kTile;
+        run[1].ntiles = run[1].lo < run[1].hi ? (run[1].hi - run[1].lo + kTile - 1) / kTile : 0;
+    }
+    const int n_fold = run[0].ntiles;
+    const int n_tiles = n_fold + run[1].ntiles;
+
+    unsigned char* kslab = lds + wave * SLAB;
+    unsigned char* vslab = kslab + KSLAB;
+    // Tile staging: every load instruction of the wavefront covers RPI whole key rows (16 bytes per
+    // lane, consecutive lanes consecutive addresses), the same pattern for K and V.
+    constexpr int LPR = D / 8;             // lanes per key row
+    constexpr int RPI = kWave / LPR;       // key rows per load instruction
+    constexpr int NVL = kTile / RPI;       // load instructions per tile and operand
+    const int v_row = lane / LPR, v_chunk = lane % LPR;
+    // transposing-read address of this lane inside the V slab: 16-lane blocks cover 4 keys x 16 d
+    const int blk = lane >> 4, i16 = lane & 15;
+    const int tr_off = ((blk >> 1) * 4 + (i16 >> 2)) * VSTRIDE + ((blk & 1) * 16 + (i16 & 3) * 4) * 2;
+
+    // The next tile is fetched into registers while the current one is being consumed from LDS.
+    // K and V are read exactly once, so the loads carry the non-temporal hint.
+    u32x4 kst[NVL], vst[NVL];
+    auto fetch = [&](int it) {
+        const KeyRun& r = run[it < n_fold ? 0 : 1];
+        const int kb_ = r.lo + (it < n_fold ? it : it - n_fold) * r.step;
+#pragma unroll
+        for (int i = 0; i < NVL; ++i) {
+            int key = kb_ + i * RPI + v_row;
+            key = key < r.hi ? key : r.hi - 1;  // a ragged last tile re-reads its last row; masked below
+            const long long off = (long long)key * r.stride_t + v_chunk * 8;
+            kst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(r.K + off));
+            vst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(r.V + off));
+        }
+    };
+    if (n_tiles > 0) fetch(0);
 
     // ---- Q fragments (B operand of S^T = K Q^T: lane = query row ln, 8 contiguous d) ----
     bf16x8 qf[NQT][KS];
-    int lim[NQT];  // keys of this segment visible to this lane's query row
+    int lim[NQT];  // keys of this wavefront's own run visible to this lane's query row
 #pragma unroll
     for (int t = 0; t < NQT; ++t) {
         const int rho = rho0 + t * kRowTile + ln;
@@ -186,7 +367,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
         const int rc = valid ? rho : rho0;
         const int b = rc / GR, rl = rc - b * GR;
         const int r = rl / prm.G, hg = rl - r * prm.G;
-        lim[t] = is_private ? causal_base + r : causal_base;
+        lim[t] = min(is_private ? causal_base + r : causal_base, run[1].hi);
         const __bf16* qp = (const __bf16*)prm.Q + (long long)b * prm.q_stride_b + (long long)r * prm.q_stride_r +
                            (long long)(kvh * prm.G + hg) * prm.q_stride_h;
 #pragma unroll
@@ -213,43 +394,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
-    unsigned char* kslab = lds + wave * SLAB;
-    unsigned char* vslab = kslab + KSLAB;
-    // Tile staging: every load instruction of the wavefront covers RPI whole key rows (16 bytes per
-    // lane, consecutive lanes consecutive addresses), the same pattern for K and V.
-    constexpr int LPR = D / 8;             // lanes per key row
-    constexpr int RPI = kWave / LPR;       // key rows per load instruction
-    constexpr int NVL = kTile / RPI;       // load instructions per tile and operand
-    const int v_row = lane / LPR, v_chunk = lane % LPR;
-    // transposing-read address of this lane inside the V slab: 16-lane blocks cover 4 keys x 16 d
-    const int blk = lane >> 4, i16 = lane & 15;
-    const int tr_off = ((blk >> 1) * 4 + (i16 >> 2)) * VSTRIDE + ((blk & 1) * 16 + (i16 & 3) * 4) * 2;
-
-    // The next tile is fetched into registers while the current one is being consumed from LDS.
-    // K and V are read exactly once, so the loads carry the non-temporal hint.
-    u32x4 kst[NVL], vst[NVL];
-    auto fetch = [&](int tile_) {
-        const int kb_ = tile_ * kTile;
-#pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-            int key = kb_ + i * RPI + v_row;
-            key = key < seg_len ? key : seg_len - 1;  // a ragged last tile re-reads the last row; masked below
-            const long long off = (long long)key * stride_t + v_chunk * 8;
-            kst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kseg + off));
-            vst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vseg + off));
-        }
-    };
-    int tile = t_lo + wave;
-    if (tile < t_hi) fetch(tile);
-
-    for (; tile < t_hi; tile += kAttnWaves) {
-        const int kbase = tile * kTile;
+    for (int it = 0; it < n_tiles; ++it) {
+        const bool folded = it < n_fold;
+        const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * kTile;
 #pragma unroll
         for (int i = 0; i < NVL; ++i) {
             *reinterpret_cast<u32x4*>(kslab + (i * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
             *reinterpret_cast<u32x4*>(vslab + (i * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
         }
-        if (tile + kAttnWaves < t_hi) fetch(tile + kAttnWaves);
+        if (it + 1 < n_tiles) fetch(it + 1);
         // K fragments (A operand of S^T = K Q^T: lane = key row ln, 8 contiguous d)
         bf16x8 kf[KS];
 #pragma unroll
@@ -265,16 +418,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[t][s], acc, 0, 0, 0);
-            // register i of this lane is key kbase + (i/4)*8 + hh*4 + i%4 for query row ln
-            const int vis = min(lim[t], seg_len) - kbase - hh * 4;  // key offsets below this are visible
+            // register i of this lane is key kbase + (i/4)*8 + hh*4 + i%4 for query row ln;
+            // every row sees all of a prefix share, the causal limit applies to the own run only
+            const int vis = (folded ? run[0].hi : lim[t]) - kbase - hh * 4;  // key offsets below this are visible
             float mx = -INFINITY;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int koff = (i >> 2) * 8 + (i & 3);
-                float s = acc[i] * prm.scale_log2;
-                s = koff < vis ? s : -INFINITY;
-                acc[i] = s;
-                mx = fmaxf(mx, s);
+                float sc = acc[i] * prm.scale_log2;
+                sc = koff < vis ? sc : -INFINITY;
+                acc[i] = sc;
+                mx = fmaxf(mx, sc);
             }
             mx = fmaxf(mx, shfl_xor_f(mx, 32));
             const float m_new = fmaxf(m_run[t], mx);
@@ -317,118 +471,82 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_partial_kernel(const Att
         }
     }
 
-    // ---- merge the 4 wavefronts' states in a fixed order, then store the item's partial ----
+    // ---- combine the 4 wavefronts' states (fixed order) and store the item's partial ----
+    // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier all 256
+    // threads form sum_w 2^(m_w - m) O_w for the valid rows and write it out, coalesced.
+    float* obuf = reinterpret_cast<float*>(lds + wave * SLAB);
+    const __amdgpu_buffer_rsrc_t rs = ws_rsrc(prm);
 #pragma unroll
     for (int t = 0; t < NQT; ++t) {
-        l_run[t] += shfl_xor_f(l_run[t], 32);
+        if (t > 0) __syncthreads();  // the previous row tile has been read out
+        const float lsum = l_run[t] + shfl_xor_f(l_run[t], 32);
         if (hh == 0) {
-            sh_m[wave][t * kRowTile + ln] = m_run[t];
-            sh_l[wave][t * kRowTile + ln] = l_run[t];
+            sh_m[wave][ln] = m_run[t];
+            sh_l[wave][ln] = lsum;
         }
-    }
-    __syncthreads();  // also: every wavefront is done with its V slab
-    float* obuf = reinterpret_cast<float*>(lds);
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) {
-        float mg = -INFINITY;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int w = 0; w < kAttnWaves; ++w) mg = fmaxf(mg, sh_m[w][t * kRowTile + ln]);
-        const float mg_use = (mg == -INFINITY) ? 0.f : mg;
-        const float wscale = __builtin_amdgcn_exp2f(m_run[t] - mg_use);
-        for (int w = 0; w < kAttnWaves; ++w) {
-            if (wave == w) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        float4* dst = reinterpret_cast<float4*>(obuf + ln * OSTRIDE + db * 32 + q4 * 8 + hh * 4);
-                        float4 v = make_float4(oacc[t][db][q4 * 4 + 0] * wscale, oacc[t][db][q4 * 4 + 1] * wscale,
-                                               oacc[t][db][q4 * 4 + 2] * wscale, oacc[t][db][q4 * 4 + 3] * wscale);
-                        if (w > 0) {
-                            const float4 o = *dst;
-                            v.x += o.x;
-                            v.y += o.y;
-                            v.z += o.z;
-                            v.w += o.w;
-                        }
-                        *dst = v;
-                    }
-            }
-            __syncthreads();
-        }
-        // cooperative store of the valid rows of this row tile
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<float4*>(obuf + ln * OSTRIDE + db * 32 + q4 * 8 + hh * 4) =
+                    make_float4(oacc[t][db][q4 * 4 + 0], oacc[t][db][q4 * 4 + 1], oacc[t][db][q4 * 4 + 2],
+                                oacc[t][db][q4 * 4 + 3]);
+        __syncthreads();
         const int nrows = min(kRowTile, rho_end - (rho0 + t * kRowTile));
         constexpr int F4 = D / 4;
         for (int e = tid; e < nrows * F4; e += kAttnThreads) {
             const int row = e / F4, c4 = e - row * F4;
-            const long long rho = rho0 + t * kRowTile + row;
-            const float4 v = *reinterpret_cast<const float4*>(obuf + row * OSTRIDE + c4 * 4);
-            float4* dst = reinterpret_cast<float4*>(
-                prm.part_o + (((long long)kvh * prm.B * GR + rho) * pl.nslots + slot) * D + c4 * 4);
-            *dst = v;
-        }
-        if (tid < nrows) {
-            const int col = t * kRowTile + tid;
-            float mrow = -INFINITY;
+            float mw[kAttnWaves], mg = -INFINITY;
 #pragma unroll
-            for (int w = 0; w < kAttnWaves; ++w) mrow = fmaxf(mrow, sh_m[w][col]);
-            const float mrow_use = (mrow == -INFINITY) ? 0.f : mrow;
-            float lrow = 0.f;
+            for (int w = 0; w < kAttnWaves; ++w) {
+                mw[w] = sh_m[w][row];
+                mg = fmaxf(mg, mw[w]);
+            }
+            const float mg_use = (mg == -INFINITY) ? 0.f : mg;
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+            float lg = 0.f;
 #pragma unroll
-            for (int w = 0; w < kAttnWaves; ++w) lrow += sh_l[w][col] * __builtin_amdgcn_exp2f(sh_m[w][col] - mrow_use);
-            const long long rho = rho0 + t * kRowTile + tid;
-            float2* dst = reinterpret_cast<float2*>(prm.part_ml + (((long long)kvh * prm.B * GR + rho) * pl.nslots + slot) * 2);
-            *dst = make_float2(mrow, lrow);
+            for (int w = 0; w < kAttnWaves; ++w) {
+                const float sc = __builtin_amdgcn_exp2f(mw[w] - mg_use);
+                const float4 v = *reinterpret_cast<const float4*>(
+                    reinterpret_cast<const float*>(lds + w * SLAB) + row * OSTRIDE + c4 * 4);
+                o.x += v.x * sc;
+                o.y += v.y * sc;
+                o.z += v.z * sc;
+                o.w += v.w * sc;
+                lg += sh_l[w][row] * sc;
+            }
+            const unsigned rho = rho0 + t * kRowTile + row;
+            const unsigned pidx = ((unsigned)kvh * prm.B * GR + rho) * pl.nslots + slot;
+            ws_store4(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
+            if (c4 == 0) ws_store2(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
         }
-        __syncthreads();
     }
-}
 
-// ---------------------------------------------------------------------------------------------
-// merge of the partials of one output row: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
-// ---------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const AttnParams prm) {
-    constexpr int TPR = D / 4;          // threads per output row, 4 floats each
-    constexpr int RPB = 256 / TPR;      // rows per block
-    const int tid = threadIdx.x;
-    const long long row = (long long)blockIdx.x * RPB + tid / TPR;
-    const int c4 = tid % TPR;
-    const long long nrows = (long long)prm.B * prm.R * prm.Hq;
-    if (row >= nrows) return;
-    const int h = (int)(row % prm.Hq);
-    const long long br = row / prm.Hq;
-    const int r = (int)(br % prm.R), b = (int)(br / prm.R);
-    const int kvh = h / prm.G, hg = h - kvh * prm.G;
-    const long long rho = (long long)b * prm.GR + r * prm.G + hg;
-    const int ns = prm.plan.nslots;
-    const long long base = ((long long)kvh * prm.B * prm.GR + rho) * ns;
-    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + base;
-    float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[s].x);
-    float Lsum = 0.f;
-    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < ns; ++s) {
-        const float2 v = ml[s];
-        const float w = __builtin_amdgcn_exp2f(v.x - M);   // a row always sees itself: M is finite
-        Lsum += v.y * w;
-        const float4 po = *reinterpret_cast<const float4*>(prm.part_o + (base + s) * D + c4 * 4);
-        o.x += po.x * w;
-        o.y += po.y * w;
-        o.z += po.z * w;
-        o.w += po.w * w;
+    // ---- arrival: whoever completes the set of partials of a (KV head, branch) merges it ----
+    // Every thread waits until its partial stores are acknowledged; then one thread per covered
+    // branch counts the arrival.  Counters start at zero and the last arrival puts the zero back.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    int* sh_last = reinterpret_cast<int*>(sh_l);  // free again; kAttnWaves * kRowTile >= rows of an item
+    const int rows_per_item = kRowTile * NQT;
+    const int b_first = rho0 / GR, b_last = (rho_end - 1) / GR;
+    const int nb = b_last - b_first + 1;  // <= rows_per_item
+    if (tid < nb) {
+        const int b = b_first + tid;
+        int expected = pl.n_rg_priv * pl.nsplit_priv;
+        if (pl.nsplit_pre > 0) {
+            const int rg_lo = (b * GR) / rows_per_item, rg_hi = ((b + 1) * GR - 1) / rows_per_item;
+            expected += pl.nsplit_pre * (rg_hi - rg_lo + 1);
+        }
+        int* cnt = prm.counters + kvh * prm.B + b;
+        const int last = (atomicAdd(cnt, 1) == expected - 1);
+        if (last) atomicExch(cnt, 0);
+        sh_last[tid] = last;
     }
-    const float inv = 1.0f / Lsum;
-    __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
-                 (long long)h * prm.o_stride_h + c4 * 4;
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-    bf16x4 ov;
-    ov[0] = (__bf16)(o.x * inv);
-    ov[1] = (__bf16)(o.y * inv);
-    ov[2] = (__bf16)(o.z * inv);
-    ov[3] = (__bf16)(o.w * inv);
-    *reinterpret_cast<bf16x4*>(op) = ov;
-    if (prm.lse && c4 == 0) prm.lse[row] = (M + log2f(Lsum)) * 0.69314718055994530942f;
+    __syncthreads();
+    for (int j = 0; j < nb; ++j)
+        if (sh_last[j]) merge_branch<D>(prm, rs, kvh, b_first + j, tid);  // uniform over the workgroup
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -546,6 +664,7 @@ static int fill_desc(const lotts_attn_desc* in, lotts_attn_desc* d) {
     if (d->q_stride_h < D || d->o_stride_h < D || d->kpre_stride_t < D || d->kpriv_stride_t < D) return LOTTS_ERR_SHAPE;
     const long long rows = (long long)d->B * R * d->Hq;
     if (rows > 0x7fffffffLL / 8) return LOTTS_ERR_SHAPE;
+    if ((long long)d->B * d->Hkv > kMaxCounters) return LOTTS_ERR_SHAPE;
     return LOTTS_OK;
 }
 
@@ -557,10 +676,8 @@ extern "C" size_t verify_attention_workspace_bytes(const lotts_attn_desc* desc) 
     if (fill_desc(desc, &d) != LOTTS_OK) return 0;
     if (d.dtype == LOTTS_F32) return 256;  // the fp32 path needs none; keep the pointer non-NULL
     const AttnPlan pl = plan_attention(d);
-    size_t bytes = part_o_elems(d, pl) * sizeof(float);
-    bytes = (bytes + 255) & ~(size_t)255;
-    bytes += part_ml_elems(d, pl) * sizeof(float);
-    return (bytes + 255) & ~(size_t)255;
+    const size_t bytes = workspace_layout(d, pl, nullptr, nullptr);
+    return bytes < 0x7fffffffULL ? bytes : 0;  // partials are addressed with 32-bit byte offsets
 }
 
 extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, const void* Kpre, const void* Vpre,
@@ -595,7 +712,7 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
 
     if (d.dtype == LOTTS_F32) {
         prm.plan = AttnPlan{};
-        prm.part_o = nullptr; prm.part_ml = nullptr;
+        prm.ws = nullptr; prm.ws_bytes = 0; prm.off_o = prm.off_ml = 0; prm.counters = nullptr;
         if (d.D == 64)
             hipLaunchKernelGGL(attn_f32_kernel<64>, dim3((unsigned)rows), dim3(kAttnThreads), 0, s, prm);
         else
@@ -605,25 +722,19 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
 
     prm.plan = plan_attention(d);
     const AttnPlan& pl = prm.plan;
-    prm.part_o = static_cast<float*>(workspace);
-    size_t off = part_o_elems(d, pl) * sizeof(float);
-    off = (off + 255) & ~(size_t)255;
-    prm.part_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off);
+    size_t off_o, off_ml;
+    const size_t total = workspace_layout(d, pl, &off_o, &off_ml);
+    prm.ws = workspace;
+    prm.ws_bytes = (unsigned)total;
+    prm.off_o = (unsigned)off_o;
+    prm.off_ml = (unsigned)off_ml;
+    prm.counters = static_cast<int*>(workspace);
     const long long items = (long long)pl.n_pre_items + pl.n_priv_items;
     if (items > 0x7fffffffLL) return LOTTS_ERR_SHAPE;
     const dim3 grid((unsigned)items), block(kAttnThreads);
-    if (d.D == 128 && pl.nqt == 1) hipLaunchKernelGGL((attn_partial_kernel<128, 1>), grid, block, 0, s, prm);
-    else if (d.D == 128) hipLaunchKernelGGL((attn_partial_kernel<128, 2>), grid, block, 0, s, prm);
-    else if (pl.nqt == 1) hipLaunchKernelGGL((attn_partial_kernel<64, 1>), grid, block, 0, s, prm);
-    else hipLaunchKernelGGL((attn_partial_kernel<64, 2>), grid, block, 0, s, prm);
-    rc = check_launch();
-    if (rc != LOTTS_OK) return rc;
-    if (d.D == 128) {
-        const int rpb = 256 / (128 / 4);
-        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, s, prm);
-    } else {
-        const int rpb = 256 / (64 / 4);
-        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, s, prm);
-    }
+    if (d.D == 128 && pl.nqt == 1) hipLaunchKernelGGL((attn_kernel<128, 1>), grid, block, 0, s, prm);
+    else if (d.D == 128) hipLaunchKernelGGL((attn_kernel<128, 2>), grid, block, 0, s, prm);
+    else if (pl.nqt == 1) hipLaunchKernelGGL((attn_kernel<64, 1>), grid, block, 0, s, prm);
+    else hipLaunchKernelGGL((attn_kernel<64, 2>), grid, block, 0, s, prm);
     return check_launch();
 }
