@@ -40,7 +40,7 @@ def accept_algorithmic_bytes(cfg, accept_len) -> int:
 
 def read_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", "attn_partial_%s_traffic.txt" % workload)
+    path = os.path.join(ROOT, "profiles", "attn_kernel_%s_traffic.txt" % workload)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):

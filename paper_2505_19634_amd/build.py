@@ -8,6 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblotts.so")
+CALIB = os.path.join(_HERE, "calib_copy")
 SOURCES = ["verify_attention.hip", "spec_accept.hip", "majority_vote.hip"]
 
 
@@ -25,6 +26,12 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    # the counter-calibration copy program (profiling aid, not part of the library)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", os.path.join(CSRC, "calib_copy.hip"), "-o", CALIB]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
     return LIB
 
 
