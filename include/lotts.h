@@ -108,6 +108,7 @@ size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V);
  * for any reduction order.  If the residual has no mass the row p_n itself is sampled; if that
  * has none either, next_token = -1.
  *
+ *   1 <= B <= 65535, 0 <= k <= 256, V >= 1
  *   p [B][k+1][V] fp32  target probabilities (finite, >= 0)
  *   q [B][k][V]   fp32  draft probabilities; NULL iff k == 0
  *   draft [B][k]  int32 draft tokens in [0, V) (the kernel clamps); NULL iff k == 0

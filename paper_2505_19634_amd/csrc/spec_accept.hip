@@ -24,11 +24,17 @@ struct AcceptPlan {
     int nchunks;  // <= kAccMaxChunks
 };
 
-static inline AcceptPlan plan_accept(int V) {
+// Chunks are sized so that the scan has about two workgroups per compute unit.
+static inline AcceptPlan plan_accept(int B, int V) {
     AcceptPlan pl;
-    pl.chunk = 2048;
-    while ((V + pl.chunk - 1) / pl.chunk > kAccMaxChunks) pl.chunk *= 2;
-    pl.nchunks = (V + pl.chunk - 1) / pl.chunk;
+    int want = (2 * kNumCU + B - 1) / B;
+    if (want > kAccMaxChunks) want = kAccMaxChunks;
+    int chunk = (V + want - 1) / want;
+    chunk = ((chunk + 4 * kAccThreads - 1) / (4 * kAccThreads)) * (4 * kAccThreads);
+    if (chunk < 2048) chunk = 2048;
+    while ((V + chunk - 1) / chunk > kAccMaxChunks) chunk *= 2;
+    pl.chunk = chunk;
+    pl.nchunks = (V + chunk - 1) / chunk;
     return pl;
 }
 
@@ -173,7 +179,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, 
         if (tid == 0) next_token[b] = -1;
         return;
     }
-    const unsigned m = (unsigned)(u[(size_t)b * (k + 1) + k] * 16777216.0f);  // trunc(u * 2^24)
+    unsigned m = (unsigned)(u[(size_t)b * (k + 1) + k] * 16777216.0f);  // trunc(u * 2^24)
+    m = m > 16777215u ? 16777215u : m;                                  // u must be < 1; keep T < Z regardless
     const unsigned long long T = (__umul64hi((unsigned long long)m, Z) << 40) | (((unsigned long long)m * Z) >> 24);
 
     // which chunk holds the crossing
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, 
 
 extern "C" size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V) {
     if (B < 1 || k < 0 || k > lotts::kAccMaxK || V < 1 || B > 65535) return 0;
-    const lotts::AcceptPlan pl = lotts::plan_accept(V);
+    const lotts::AcceptPlan pl = lotts::plan_accept(B, V);
     return (size_t)2 * B * pl.nchunks * sizeof(unsigned long long);
 }
 
@@ -233,7 +240,7 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
     if (k > 0 && (!q || !draft)) return LOTTS_ERR_NULL;
     if (workspace_bytes < spec_accept_workspace_bytes(B, k, V)) return LOTTS_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 7) != 0) return LOTTS_ERR_SHAPE;
-    const AcceptPlan pl = plan_accept(V);
+    const AcceptPlan pl = plan_accept(B, V);
     unsigned long long* sums = static_cast<unsigned long long*>(workspace);
     hipStream_t s = (hipStream_t)stream;
     // float4 loads need every row start 16-byte aligned

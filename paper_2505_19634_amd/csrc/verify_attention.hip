@@ -46,7 +46,7 @@ constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kTile = 32;      // keys per tile = M of one 32x32x16 MFMA
 constexpr int kRowTile = 32;   // query rows per row tile = N of the MFMA
-constexpr int kMaxSplit = 64;
+constexpr int kMaxSplit = 16;  // more key shares than this cost more in the merge than they gain in streaming
 
 struct AttnPlan {
     int nqt;            // row tiles per item: 1 or 2
@@ -56,6 +56,7 @@ struct AttnPlan {
     int nsplit_priv;    // key splits of a private segment
     int nsplit_pre;     // key splits of the prefix (stacked plan; 0 otherwise)
     int nslots;         // partials per output row
+    int fused;          // 1: the last-arriving workgroup merges inside the attention launch
     int n_pre_items, n_priv_items;
 };
 
@@ -76,6 +77,9 @@ struct AttnParams {
     long long kpriv_stride_b, kpriv_stride_h, kpriv_stride_t;
     long long o_stride_b, o_stride_r, o_stride_h;
     AttnPlan plan;
+#ifdef LOTTS_TUNING
+    long long* dbg;  // development builds: per-workgroup phase timestamps
+#endif
 };
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -118,6 +122,13 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
         pl.nsplit_pre = 0;
     }
     pl.nslots = pl.nsplit_pre + pl.nsplit_priv;
+    // The in-launch merge of a (KV head, branch) is done by ONE workgroup, at one CU's share of the
+    // bandwidth: worth it only while that is a few tens of KB; beyond, a separate launch spreads the
+    // merge over the whole chip.
+    pl.fused = ((long long)pl.nslots * GR * d.D * 4 <= 48 * 1024) ? 1 : 0;
+#ifdef LOTTS_TUNING
+    if (const char* e = getenv("LOTTS_FUSED")) pl.fused = atoi(e);
+#endif
     pl.n_pre_items = d.Hkv * pl.n_rg_pre * pl.nsplit_pre;
     pl.n_priv_items = d.B * d.Hkv * pl.n_rg_priv * pl.nsplit_priv;
     return pl;
@@ -144,82 +155,116 @@ static inline size_t workspace_layout(const lotts_attn_desc& d, const AttnPlan& 
     return (bytes + 255) & ~(size_t)255;
 }
 
-// 16- and 8-byte accesses to the workspace with the device-scope cache policy (sc0 sc1).
+// 16- and 8-byte accesses to the workspace, with the device-scope cache policy (sc0 sc1) when the
+// data crosses workgroups inside one launch, plain otherwise.
 constexpr int kDevScope = 17;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t ws_rsrc(const AttnParams& prm) {
     return __builtin_amdgcn_make_buffer_rsrc(prm.ws, 0, (int)prm.ws_bytes, 0x00020000);
 }
+template <bool DEV>
 __device__ __forceinline__ void ws_store4(__amdgpu_buffer_rsrc_t r, unsigned byte_off, float4 v) {
     u32x4 u;
     u[0] = __float_as_uint(v.x); u[1] = __float_as_uint(v.y); u[2] = __float_as_uint(v.z); u[3] = __float_as_uint(v.w);
-    __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, kDevScope);
+    __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, DEV ? kDevScope : 0);
 }
+template <bool DEV>
 __device__ __forceinline__ void ws_store2(__amdgpu_buffer_rsrc_t r, unsigned byte_off, float2 v) {
     u32x2 u;
     u[0] = __float_as_uint(v.x); u[1] = __float_as_uint(v.y);
-    __builtin_amdgcn_raw_buffer_store_b64(u, r, (int)byte_off, 0, kDevScope);
+    __builtin_amdgcn_raw_buffer_store_b64(u, r, (int)byte_off, 0, DEV ? kDevScope : 0);
 }
+template <bool DEV>
 __device__ __forceinline__ float4 ws_load4(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
-    const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kDevScope);
+    const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, DEV ? kDevScope : 0);
     return make_float4(__uint_as_float(u[0]), __uint_as_float(u[1]), __uint_as_float(u[2]), __uint_as_float(u[3]));
 }
+template <bool DEV>
 __device__ __forceinline__ float2 ws_load2(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
-    const u32x2 u = __builtin_amdgcn_raw_buffer_load_b64(r, (int)byte_off, 0, kDevScope);
+    const u32x2 u = __builtin_amdgcn_raw_buffer_load_b64(r, (int)byte_off, 0, DEV ? kDevScope : 0);
     return make_float2(__uint_as_float(u[0]), __uint_as_float(u[1]));
 }
 
 // ---------------------------------------------------------------------------------------------
 // Merge of the partials of the G*R output rows of one (KV head, branch), run by the workgroup that
 // delivered the last of them:  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// 4 floats per thread; the partials are taken 4 slots at a time so their loads go out together.
+// 4 floats per output quad; a thread takes two quads and 8 slots at a time so that 16 sixteen-byte
+// loads are in flight together.  DEV selects device-scope loads (merge inside the attention launch,
+// partials come from the memory side of the L2s) or plain loads (separate merge launch).
 // ---------------------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buffer_rsrc_t rs, int kvh, int b, int tid) {
+template <int D, bool DEV>
+__device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buffer_rsrc_t rs, int kvh, int b, int tid,
+                                             int e_begin, int e_end) {
     constexpr int F4 = D / 4;
-    constexpr int CH = 4;
+    constexpr int CH = 8;  // slots per round of loads
+    constexpr int EU = 2;  // output quads handled together: 2 * 8 sixteen-byte loads in flight per thread
     const int ns = prm.plan.nslots;
-    for (int e = tid; e < prm.GR * F4; e += kAttnThreads) {
-        const int rl = e / F4, c4 = e - rl * F4;
-        const int r = rl / prm.G, hg = rl - r * prm.G;
-        const int h = kvh * prm.G + hg;
-        const unsigned base = ((unsigned)kvh * prm.B * prm.GR + (unsigned)b * prm.GR + rl) * ns;
-        float M = -INFINITY, Lsum = 0.f;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s0 = 0; s0 < ns; s0 += CH) {
-            float2 mv[CH];
-            float4 pv[CH];
+    const int n_e = e_end < prm.GR * F4 ? e_end : prm.GR * F4;  // output quads [e_begin, e_end) of this (KV head, branch)
+    for (int e0 = e_begin + tid; e0 < n_e; e0 += EU * kAttnThreads) {
+        int rl[EU], c4[EU];
+        unsigned base[EU];
+        bool ok[EU];
+        float M[EU], Lsum[EU];
+        float4 o[EU];
 #pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const bool in = s0 + j < ns;
-                mv[j] = in ? ws_load2(rs, prm.off_ml + (base + s0 + j) * 8u) : make_float2(-INFINITY, 0.f);
-                pv[j] = in ? ws_load4(rs, prm.off_o + ((base + s0 + j) * D + c4 * 4) * 4u) : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-            float Mn = M;
-#pragma unroll
-            for (int j = 0; j < CH; ++j) Mn = fmaxf(Mn, mv[j].x);
-            const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
-            const float a = __builtin_amdgcn_exp2f(M - Mu);
-            Lsum *= a;
-            o.x *= a; o.y *= a; o.z *= a; o.w *= a;
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const float w = __builtin_amdgcn_exp2f(mv[j].x - Mu);
-                Lsum += mv[j].y * w;
-                o.x += pv[j].x * w; o.y += pv[j].y * w; o.z += pv[j].z * w; o.w += pv[j].w * w;
-            }
-            M = Mn;
+        for (int q = 0; q < EU; ++q) {
+            const int e = e0 + q * kAttnThreads;
+            ok[q] = e < n_e;
+            const int ec = ok[q] ? e : e0;
+            rl[q] = ec / F4;
+            c4[q] = ec - rl[q] * F4;
+            base[q] = ((unsigned)kvh * prm.B * prm.GR + (unsigned)b * prm.GR + rl[q]) * ns;
+            M[q] = -INFINITY;
+            Lsum[q] = 0.f;
+            o[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        const float inv = 1.0f / Lsum;  // a row always sees itself: Lsum > 0
-        __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
-                     (long long)h * prm.o_stride_h + c4 * 4;
-        bf16x4 ov;
-        ov[0] = (__bf16)(o.x * inv);
-        ov[1] = (__bf16)(o.y * inv);
-        ov[2] = (__bf16)(o.z * inv);
-        ov[3] = (__bf16)(o.w * inv);
-        *reinterpret_cast<bf16x4*>(op) = ov;
-        if (prm.lse && c4 == 0)
-            prm.lse[((long long)b * prm.R + r) * prm.Hq + h] = (M + log2f(Lsum)) * 0.69314718055994530942f;
+        for (int s0 = 0; s0 < ns; s0 += CH) {
+            float2 mv[EU][CH];
+            float4 pv[EU][CH];
+#pragma unroll
+            for (int q = 0; q < EU; ++q)
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const bool in = s0 + j < ns;
+                    mv[q][j] = in ? ws_load2<DEV>(rs, prm.off_ml + (base[q] + s0 + j) * 8u) : make_float2(-INFINITY, 0.f);
+                    pv[q][j] = in ? ws_load4<DEV>(rs, prm.off_o + ((base[q] + s0 + j) * D + c4[q] * 4) * 4u)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+            for (int q = 0; q < EU; ++q) {
+                float Mn = M[q];
+#pragma unroll
+                for (int j = 0; j < CH; ++j) Mn = fmaxf(Mn, mv[q][j].x);
+                const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
+                const float a = __builtin_amdgcn_exp2f(M[q] - Mu);
+                Lsum[q] *= a;
+                o[q].x *= a; o[q].y *= a; o[q].z *= a; o[q].w *= a;
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const float w = __builtin_amdgcn_exp2f(mv[q][j].x - Mu);
+                    Lsum[q] += mv[q][j].y * w;
+                    o[q].x += pv[q][j].x * w; o[q].y += pv[q][j].y * w;
+                    o[q].z += pv[q][j].z * w; o[q].w += pv[q][j].w * w;
+                }
+                M[q] = Mn;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < EU; ++q) {
+            if (!ok[q]) continue;
+            const int r = rl[q] / prm.G, hg = rl[q] - r * prm.G;
+            const int h = kvh * prm.G + hg;
+            const float inv = 1.0f / Lsum[q];  // a row always sees itself: Lsum > 0
+            __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
+                         (long long)h * prm.o_stride_h + c4[q] * 4;
+            bf16x4 ov;
+            ov[0] = (__bf16)(o[q].x * inv);
+            ov[1] = (__bf16)(o[q].y * inv);
+            ov[2] = (__bf16)(o[q].z * inv);
+            ov[3] = (__bf16)(o[q].w * inv);
+            *reinterpret_cast<bf16x4*>(op) = ov;
+            if (prm.lse && c4[q] == 0)
+                prm.lse[((long long)b * prm.R + r) * prm.Hq + h] = (M[q] + log2f(Lsum[q])) * 0.69314718055994530942f;
+        }
     }
 }
 
@@ -239,7 +284,7 @@ struct KeyRun {
 // bf16 partial attention
 // ---------------------------------------------------------------------------------------------
 template <int D, int NQT>
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams prm) {
+__global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(const AttnParams prm) {
     constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide blocks of the head dimension
     constexpr int KSTRIDE = D * 2 + 16;    // bytes per key row of the K slab (pad: conflict-free 16-byte row reads)
@@ -256,13 +301,21 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31;   // MFMA column (query row) / A row (key or d) owned by this lane
     const int hh = lane >> 5;   // which half of each 16-wide k block this lane holds
+#ifdef LOTTS_TUNING
+#define DBG_STAMP(i) do { if (prm.dbg && tid == 0) prm.dbg[(long long)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define DBG_STAMP(i)
+#endif
     const AttnPlan& pl = prm.plan;
     const int GR = prm.GR;
+    DBG_STAMP(0);
 
     // ---- decode the work item: private items first (one per CU starts at once), prefix items after ----
+    // Order matters for latency: whatever does not depend on priv_len[b] (the prefix share, the Q
+    // rows) is requested before that value is first used.
     int id = blockIdx.x;
     const bool is_private = id < pl.n_priv_items;
-    int kvh, split, nsplit, rho0, rho_end, seg_len, slot, causal_base;
+    int kvh, split, nsplit, rho0, rho_end, slot, b_item = 0;
     KeyRun run[2];   // run[0]: folded prefix share (may be empty), run[1]: the item's own segment
     run[0].ntiles = 0;
     if (is_private) {
@@ -271,32 +324,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
         split = rest % pl.nsplit_priv;
         rest /= pl.nsplit_priv;
         const int rg = rest % pl.n_rg_priv;
-        const int b = rest / pl.n_rg_priv;
+        b_item = rest / pl.n_rg_priv;
         nsplit = pl.nsplit_priv;
-        rho0 = b * GR + rg * kRowTile * NQT;
-        rho_end = min((b + 1) * GR, rho0 + kRowTile * NQT);
-        int L = prm.priv_len[b];
-        L = L < prm.R ? prm.R : (L > prm.Lmax ? prm.Lmax : L);
-        seg_len = L;
-        causal_base = L - prm.k;  // row at position r sees private keys [0, L - k + r)
-        const long long off = (long long)b * prm.kpriv_stride_b + (long long)kvh * prm.kpriv_stride_h;
-        run[1].K = (const __bf16*)prm.Kpriv + off;
-        run[1].V = (const __bf16*)prm.Vpriv + off;
-        run[1].stride_t = prm.kpriv_stride_t;
+        rho0 = b_item * GR + rg * kRowTile * NQT;
+        rho_end = min((b_item + 1) * GR, rho0 + kRowTile * NQT);
         slot = pl.nsplit_pre + split;
-        if (pl.fold) {
-            // this item's share of the prefix keys (groups of 4), dealt to the wavefronts tile by tile
-            const int pg = (prm.P + 3) >> 2;
-            const int p_lo = (int)((long long)split * pg / nsplit) * 4;
-            const int p_hi = min(prm.P, (int)((long long)(split + 1) * pg / nsplit) * 4);
-            run[0].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
-            run[0].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
-            run[0].stride_t = prm.kpre_stride_t;
-            run[0].lo = p_lo + wave * kTile;
-            run[0].hi = p_hi;
-            run[0].step = kAttnWaves * kTile;
-            run[0].ntiles = run[0].lo < p_hi ? (p_hi - run[0].lo + run[0].step - 1) / run[0].step : 0;
-        }
     } else {
         id -= pl.n_priv_items;
         kvh = id % prm.Hkv;
@@ -306,27 +338,23 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
         nsplit = pl.nsplit_pre;
         rho0 = rg * kRowTile * NQT;
         rho_end = min(prm.B * GR, rho0 + kRowTile * NQT);
-        seg_len = prm.P;
-        causal_base = prm.P;  // every row sees the whole prefix
-        run[1].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
-        run[1].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
-        run[1].stride_t = prm.kpre_stride_t;
         slot = split;
     }
-    // Keys of the item's own segment are dealt out in groups of 4 (one load instruction covers whole
-    // groups): the item takes an equal share of the groups and each of its wavefronts an equal,
-    // contiguous share of those, so all wavefronts stream the same number of bytes to within 4 keys.
-    {
-        const int ngroups = (seg_len + 3) >> 2;
-        const int g_lo = (int)((long long)split * ngroups / nsplit);
-        const int g_hi = (int)((long long)(split + 1) * ngroups / nsplit);
-        run[1].lo = (g_lo + (int)((long long)wave * (g_hi - g_lo) / kAttnWaves)) * 4;
-        run[1].hi = min(seg_len, (g_lo + (int)((long long)(wave + 1) * (g_hi - g_lo) / kAttnWaves)) * 4);
-        run[1].step = kTile;
-        run[1].ntiles = run[1].lo < run[1].hi ? (run[1].hi - run[1].lo + kTile - 1) / kTile : 0;
+    const int L_raw = is_private ? prm.priv_len[b_item] : 0;  // requested here, first used further down
+    if (is_private && pl.fold) {
+        // this item's share of the prefix keys (groups of 4), dealt to the wavefronts tile by tile
+        const int pg = (prm.P + 3) >> 2;
+        const int p_lo = (int)((long long)split * pg / nsplit) * 4;
+        const int p_hi = min(prm.P, (int)((long long)(split + 1) * pg / nsplit) * 4);
+        run[0].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
+        run[0].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
+        run[0].stride_t = prm.kpre_stride_t;
+        run[0].lo = p_lo + wave * kTile;
+        run[0].hi = p_hi;
+        run[0].step = kAttnWaves * kTile;
+        run[0].ntiles = run[0].lo < p_hi ? (p_hi - run[0].lo + run[0].step - 1) / run[0].step : 0;
     }
     const int n_fold = run[0].ntiles;
-    const int n_tiles = n_fold + run[1].ntiles;
 
     unsigned char* kslab = lds + wave * SLAB;
     unsigned char* vslab = kslab + KSLAB;
@@ -355,11 +383,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
             vst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(r.V + off));
         }
     };
-    if (n_tiles > 0) fetch(0);
+    if (n_fold > 0) fetch(0);
 
     // ---- Q fragments (B operand of S^T = K Q^T: lane = query row ln, 8 contiguous d) ----
     bf16x8 qf[NQT][KS];
-    int lim[NQT];  // keys of this wavefront's own run visible to this lane's query row
+    int q_r[NQT];  // position (0..k) of this lane's query row
 #pragma unroll
     for (int t = 0; t < NQT; ++t) {
         const int rho = rho0 + t * kRowTile + ln;
@@ -367,7 +395,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
         const int rc = valid ? rho : rho0;
         const int b = rc / GR, rl = rc - b * GR;
         const int r = rl / prm.G, hg = rl - r * prm.G;
-        lim[t] = min(is_private ? causal_base + r : causal_base, run[1].hi);
+        q_r[t] = r;
         const __bf16* qp = (const __bf16*)prm.Q + (long long)b * prm.q_stride_b + (long long)r * prm.q_stride_r +
                            (long long)(kvh * prm.G + hg) * prm.q_stride_h;
 #pragma unroll
@@ -380,6 +408,41 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
             qf[t][s] = v;
         }
     }
+
+    // ---- the item's own segment ----
+    int seg_len, causal_base;
+    if (is_private) {
+        const int L = L_raw < prm.R ? prm.R : (L_raw > prm.Lmax ? prm.Lmax : L_raw);
+        seg_len = L;
+        causal_base = L - prm.k;  // row at position r sees private keys [0, L - k + r)
+        const long long off = (long long)b_item * prm.kpriv_stride_b + (long long)kvh * prm.kpriv_stride_h;
+        run[1].K = (const __bf16*)prm.Kpriv + off;
+        run[1].V = (const __bf16*)prm.Vpriv + off;
+        run[1].stride_t = prm.kpriv_stride_t;
+    } else {
+        seg_len = prm.P;
+        causal_base = prm.P;  // every row sees the whole prefix
+        run[1].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
+        run[1].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
+        run[1].stride_t = prm.kpre_stride_t;
+    }
+    // Keys of the item's own segment are dealt out in groups of 4 (one load instruction covers whole
+    // groups): the item takes an equal share of the groups and each of its wavefronts an equal,
+    // contiguous share of those, so all wavefronts stream the same number of bytes to within 4 keys.
+    {
+        const int ngroups = (seg_len + 3) >> 2;
+        const int g_lo = (int)((long long)split * ngroups / nsplit);
+        const int g_hi = (int)((long long)(split + 1) * ngroups / nsplit);
+        run[1].lo = (g_lo + (int)((long long)wave * (g_hi - g_lo) / kAttnWaves)) * 4;
+        run[1].hi = min(seg_len, (g_lo + (int)((long long)(wave + 1) * (g_hi - g_lo) / kAttnWaves)) * 4);
+        run[1].step = kTile;
+        run[1].ntiles = run[1].lo < run[1].hi ? (run[1].hi - run[1].lo + kTile - 1) / kTile : 0;
+    }
+    const int n_tiles = n_fold + run[1].ntiles;
+    if (n_fold == 0 && n_tiles > 0) fetch(0);
+    int lim[NQT];  // keys of this wavefront's own run visible to this lane's query row
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) lim[t] = min(is_private ? causal_base + q_r[t] : causal_base, run[1].hi);
 
     // ---- running state ----
     f32x16 oacc[NQT][DB];
@@ -394,7 +457,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
+    DBG_STAMP(1);
     for (int it = 0; it < n_tiles; ++it) {
+        if (it == 1) DBG_STAMP(2);
         const bool folded = it < n_fold;
         const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * kTile;
 #pragma unroll
@@ -471,6 +536,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
         }
     }
 
+    DBG_STAMP(3);
     // ---- combine the 4 wavefronts' states (fixed order) and store the item's partial ----
     // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier all 256
     // threads form sum_w 2^(m_w - m) O_w for the valid rows and write it out, coalesced.
@@ -518,16 +584,24 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
             }
             const unsigned rho = rho0 + t * kRowTile + row;
             const unsigned pidx = ((unsigned)kvh * prm.B * GR + rho) * pl.nslots + slot;
-            ws_store4(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
-            if (c4 == 0) ws_store2(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+            if (pl.fused) {
+                ws_store4<true>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
+                if (c4 == 0) ws_store2<true>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+            } else {
+                ws_store4<false>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
+                if (c4 == 0) ws_store2<false>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+            }
         }
     }
 
+    if (!pl.fused) return;  // a separate launch merges (many partials per row: one workgroup would be too slow)
     // ---- arrival: whoever completes the set of partials of a (KV head, branch) merges it ----
     // Every thread waits until its partial stores are acknowledged; then one thread per covered
     // branch counts the arrival.  Counters start at zero and the last arrival puts the zero back.
+    DBG_STAMP(4);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    DBG_STAMP(5);
     int* sh_last = reinterpret_cast<int*>(sh_l);  // free again; kAttnWaves * kRowTile >= rows of an item
     const int rows_per_item = kRowTile * NQT;
     const int b_first = rho0 / GR, b_last = (rho_end - 1) / GR;
@@ -545,8 +619,22 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_kernel(const AttnParams 
         sh_last[tid] = last;
     }
     __syncthreads();
+    DBG_STAMP(6);
     for (int j = 0; j < nb; ++j)
-        if (sh_last[j]) merge_branch<D>(prm, rs, kvh, b_first + j, tid);  // uniform over the workgroup
+        if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
+    __builtin_amdgcn_s_waitcnt(0);
+    DBG_STAMP(7);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Separate merge launch, used when a row has many partials: grid (quads of a (KV head, branch) in
+// blocks of 256, KV head x branch), one output quad per thread, so the whole chip shares the reads.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kAttnThreads) void attn_merge_kernel(const AttnParams prm) {
+    const int kvh = blockIdx.y % prm.Hkv, b = blockIdx.y / prm.Hkv;
+    const int e_begin = blockIdx.x * kAttnThreads;
+    merge_branch<D, false>(prm, ws_rsrc(prm), kvh, b, threadIdx.x, e_begin, e_begin + kAttnThreads);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -707,6 +795,9 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     prm.kpre_stride_h = d.kpre_stride_h; prm.kpre_stride_t = d.kpre_stride_t;
     prm.kpriv_stride_b = d.kpriv_stride_b; prm.kpriv_stride_h = d.kpriv_stride_h; prm.kpriv_stride_t = d.kpriv_stride_t;
     prm.o_stride_b = d.o_stride_b; prm.o_stride_r = d.o_stride_r; prm.o_stride_h = d.o_stride_h;
+#ifdef LOTTS_TUNING
+    prm.dbg = getenv("LOTTS_DBG_PTR") ? (long long*)strtoull(getenv("LOTTS_DBG_PTR"), nullptr, 0) : nullptr;
+#endif
     hipStream_t s = (hipStream_t)stream;
     const long long rows = (long long)d.B * prm.R * d.Hq;
 
@@ -736,5 +827,12 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     else if (d.D == 128) hipLaunchKernelGGL((attn_kernel<128, 2>), grid, block, 0, s, prm);
     else if (pl.nqt == 1) hipLaunchKernelGGL((attn_kernel<64, 1>), grid, block, 0, s, prm);
     else hipLaunchKernelGGL((attn_kernel<64, 2>), grid, block, 0, s, prm);
+    if (!pl.fused) {
+        rc = check_launch();
+        if (rc != LOTTS_OK) return rc;
+        const dim3 mgrid((unsigned)((prm.GR * (d.D / 4) + kAttnThreads - 1) / kAttnThreads), (unsigned)(d.Hkv * d.B));
+        if (d.D == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, block, 0, s, prm);
+        else hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, block, 0, s, prm);
+    }
     return check_launch();
 }
