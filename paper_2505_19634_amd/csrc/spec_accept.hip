@@ -24,17 +24,12 @@ struct AcceptPlan {
     int nchunks;  // <= kAccMaxChunks
 };
 
-// Chunks are sized so that the scan has about two workgroups per compute unit.
-static inline AcceptPlan plan_accept(int B, int V) {
+// 2048-token chunks (8 tokens per thread) unless the vocabulary needs more than kAccMaxChunks of them.
+static inline AcceptPlan plan_accept(int V) {
     AcceptPlan pl;
-    int want = (2 * kNumCU + B - 1) / B;
-    if (want > kAccMaxChunks) want = kAccMaxChunks;
-    int chunk = (V + want - 1) / want;
-    chunk = ((chunk + 4 * kAccThreads - 1) / (4 * kAccThreads)) * (4 * kAccThreads);
-    if (chunk < 2048) chunk = 2048;
-    while ((V + chunk - 1) / chunk > kAccMaxChunks) chunk *= 2;
-    pl.chunk = chunk;
-    pl.nchunks = (V + chunk - 1) / chunk;
+    pl.chunk = 2048;
+    while ((V + pl.chunk - 1) / pl.chunk > kAccMaxChunks) pl.chunk *= 2;
+    pl.nchunks = (V + pl.chunk - 1) / pl.chunk;
     return pl;
 }
 
@@ -149,7 +144,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_scan_kernel(int B, int k, 
     }
 }
 
-__global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, int V, int chunk, int nchunks,
+__global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, int V, int chunk, int nchunks, bool vec,
                                                                   const float* __restrict__ p,
                                                                   const float* __restrict__ q,
                                                                   const float* __restrict__ u,
@@ -207,6 +202,36 @@ __global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, 
     const int ept = chunk / kAccThreads;
     const int lo = c * chunk + tid * ept;
     const int hi = (lo + ept < V) ? lo + ept : V;
+    if (vec && ept == 8 && (c + 1) * chunk <= V) {  // uniform over the workgroup: both paths hold barriers
+        // common case (a full chunk): the 8 weights stay in registers between the scan and the walk
+        const float4 p0 = *reinterpret_cast<const float4*>(prow + lo), p1 = *reinterpret_cast<const float4*>(prow + lo + 4);
+        float4 q0 = make_float4(0.f, 0.f, 0.f, 0.f), q1 = q0;
+        if (use_res) {
+            q0 = *reinterpret_cast<const float4*>(qrow + lo);
+            q1 = *reinterpret_cast<const float4*>(qrow + lo + 4);
+        }
+        const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        const float qv[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        unsigned long long w[8], local = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w[i] = fixed_weight(use_res ? residual(pv[i], qv[i]) : pv[i]);
+            local += w[i];
+        }
+        unsigned long long run = base + block_excl_scan(local, sh_scan);
+        if (run <= T && T < run + local) {
+            int tok = lo;
+#pragma unroll
+            for (int i = 7; i >= 0; --i) {  // the first i whose inclusive prefix exceeds T
+                unsigned long long pre = run;
+#pragma unroll
+                for (int j = 0; j <= i; ++j) pre += w[j];
+                if (pre > T) tok = lo + i;
+            }
+            next_token[b] = tok;
+        }
+        return;
+    }
     unsigned long long local = 0;
     for (int i = lo; i < hi; ++i) local += fixed_weight(use_res ? residual(prow[i], qrow[i]) : prow[i]);
     unsigned long long run = base + block_excl_scan(local, sh_scan);
@@ -227,7 +252,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, 
 
 extern "C" size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V) {
     if (B < 1 || k < 0 || k > lotts::kAccMaxK || V < 1 || B > 65535) return 0;
-    const lotts::AcceptPlan pl = lotts::plan_accept(B, V);
+    const lotts::AcceptPlan pl = lotts::plan_accept(V);
     return (size_t)2 * B * pl.nchunks * sizeof(unsigned long long);
 }
 
@@ -240,7 +265,7 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
     if (k > 0 && (!q || !draft)) return LOTTS_ERR_NULL;
     if (workspace_bytes < spec_accept_workspace_bytes(B, k, V)) return LOTTS_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 7) != 0) return LOTTS_ERR_SHAPE;
-    const AcceptPlan pl = plan_accept(B, V);
+    const AcceptPlan pl = plan_accept(V);
     unsigned long long* sums = static_cast<unsigned long long*>(workspace);
     hipStream_t s = (hipStream_t)stream;
     // float4 loads need every row start 16-byte aligned
@@ -254,7 +279,7 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
                            q, draft, u, accept_len, sums);
     int rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    hipLaunchKernelGGL(accept_pick_kernel, dim3(B), dim3(kAccThreads), 0, s, B, k, V, pl.chunk, pl.nchunks, p, q, u,
+    hipLaunchKernelGGL(accept_pick_kernel, dim3(B), dim3(kAccThreads), 0, s, B, k, V, pl.chunk, pl.nchunks, vec, p, q, u,
                        accept_len, sums, next_token);
     return check_launch();
 }

@@ -55,7 +55,7 @@ def test_workspace_queries(lib):
     need = lib.verify_attention_workspace_bytes(ctypes.byref(d))
     assert 0 < need < 64 << 20 and need % 256 == 0
     for bad in (dict(Hq=41), dict(D=96), dict(k=-1), dict(B=0), dict(Lmax=3), dict(dtype=7), dict(P=-1),
-                dict(q_stride_h=12)):
+                dict(q_stride_h=12), dict(B=4096, Hkv=8, Hq=8)):
         assert lib.verify_attention_workspace_bytes(ctypes.byref(make_desc(**bad))) == 0, bad
     assert lib.verify_attention_workspace_bytes(None) == 0
     assert lib.spec_accept_workspace_bytes(16, 3, 152064) > 0

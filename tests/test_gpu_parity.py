@@ -49,6 +49,10 @@ SMALL_ATTN = [
     BF.with_(B=4, Hq=8, Hkv=4, D=64, P=100, L=333, k=3),             # head_dim 64
     BF.with_(B=2, Hq=12, Hkv=2, D=64, k=6, P=31, L=95),              # head_dim 64, two row tiles
     BF.with_(B=37, Hq=4, Hkv=4, k=1, P=300, L=65),                   # many branches stacked on the prefix
+    BF.with_(B=8, P=2048, L=512),                                    # long prefix: stacked plan, several prefix splits
+    BF.with_(B=5, Hq=16, Hkv=2, k=4, P=1500, L=300),                 # stacked plan with two row tiles per item
+    BF.with_(B=2, Hq=16, Hkv=2, k=2, P=64, L=4000),                  # few (head, branch) pairs: 16 key splits, separate merge launch
+    BF.with_(B=3, Hq=8, Hkv=8, k=0, P=16, L=1000),                   # k = 0 with folded prefix shorter than a tile
 ]
 
 
@@ -86,6 +90,26 @@ def test_attention_token_major_layout(lotts, oracle):
     Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
     e_abs, e_fro, _ = attn_errors(O, Oref)
     assert e_abs <= 2e-2 and e_fro <= 1e-2
+
+
+def test_attention_workspace_survives_geometry_changes(lotts, oracle):
+    """One caller-owned workspace, zero-filled once, serves calls of different geometry in any order:
+    every call leaves the arrival counters zero."""
+    import ctypes
+    from paper_2505_19634_amd import binding
+    lib = binding.load()
+    ws = torch.zeros(32 << 20, dtype=torch.uint8, device=DEV)
+    cases = [BF.with_(B=3, P=96, L=200), BF.with_(B=37, Hq=4, Hkv=4, k=1, P=300, L=65), BF.with_(B=2, P=0, L=131),
+             BF.with_(B=2, Hq=16, Hkv=2, k=2, P=64, L=4000), BF.with_(B=3, P=96, L=200)]
+    for cfg in cases:
+        a = S.attention_inputs(cfg)
+        d = attn_to_dev(cfg, a)
+        O = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"], workspace=ws)
+        torch.cuda.synchronize()
+        Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
+        e_abs, e_fro, _ = attn_errors(O, Oref)
+        assert e_abs <= 2e-2 and e_fro <= 1e-2, cfg
+        assert int(ws[:65536].view(torch.int32).abs().sum()) == 0
 
 
 def test_attention_is_deterministic(lotts):
