@@ -264,3 +264,212 @@ int oracle_majority_vote(int N, int B, const int32_t *answers, int32_t *winner, 
     }
     return 0;
 }
+
+/* =====================================================================================
+ * Widening 1: acceptance straight from logits (no materialised p, q).
+ *
+ * The distributions are softmax(z * inv_temp) of the target / draft logits (Section 2: the
+ * draft proposes, the target verifies; the paper states no temperature, so it is an argument).
+ * To stay independent of summation order AND of the platform's exp(), the softmax is defined
+ * through integers: for a row with y_v = fp32(z_v) * inv_temp and m = max_v y_v,
+ *     t_v = (y_v - m) * log2(e)                      two fp32 operations
+ *     E_v = trunc( P(frac(-t_v)) * 2^(30 - floor(-t_v)) ),  0 if floor(-t_v) >= 31
+ * where P is a fixed degree-6 polynomial for 2^-f on [0,1) evaluated by fused multiply-adds
+ * (relative error 1.4e-7), S = sum_v E_v, and the probability of v is E_v / S exactly.
+ * Accept draft x iff U * Eq(x) * Sp < 2^24 * Ep(x) * Sq with U = trunc(u * 2^24) (this is
+ * u < min(1, p/q) on the rationals); residual weights W_v = max(0, Ep_v * Sq - Eq_v * Sp),
+ * bonus weights W_v = Ep_v; token = first v with prefix sum > floor(U_k * sum W / 2^24).
+ * 128-bit integers throughout; V <= 2^20.
+ * ===================================================================================== */
+static float pow2_neg_poly(float f)
+{
+    /* 2^-f on [0, 1): coefficients fixed by this specification (c0 = 1 exactly) */
+    float g = 0x1.e243bep-14f;
+    g = fmaf(g, f, -0x1.52a284p-10f);
+    g = fmaf(g, f, 0x1.3a7ae4p-7f);
+    g = fmaf(g, f, -0x1.c6a66cp-5f);
+    g = fmaf(g, f, 0x1.ebfbaap-3f);
+    g = fmaf(g, f, -0x1.62e430p-1f);
+    g = fmaf(g, f, 1.0f);
+    return g;
+}
+
+static uint64_t logit_weight(float y, float m)
+{
+    float t = (y - m) * 0x1.715476p+0f; /* log2(e) */
+    float a = -t;
+    float nf = floorf(a);
+    if (!(nf < 31.0f))
+        return 0;
+    float f = a - nf;
+    float g = pow2_neg_poly(f);
+    return (uint64_t)(g * ldexpf(1.0f, 30 - (int)nf));
+}
+
+static float logit_at(const void *z, int dtype, int64_t idx, float inv_temp)
+{
+    return (float)load_elem(z, dtype, idx) * inv_temp;
+}
+
+/* Integer softmax weights of one row of V logits (exposed for the tests): E[V], returns S. */
+uint64_t oracle_logit_weights(int V, const void *z, int dtype, float inv_temp, uint64_t *E)
+{
+    float m = logit_at(z, dtype, 0, inv_temp);
+    for (int v = 1; v < V; ++v) {
+        float y = logit_at(z, dtype, v, inv_temp);
+        if (y > m)
+            m = y;
+    }
+    uint64_t S = 0;
+    for (int v = 0; v < V; ++v) {
+        E[v] = logit_weight(logit_at(z, dtype, v, inv_temp), m);
+        S += E[v];
+    }
+    return S;
+}
+
+typedef unsigned __int128 u128;
+
+int oracle_spec_accept_logits(int B, int k, int V, const void *zt, const void *zd, int dtype, float inv_temp,
+                              const int32_t *draft, const float *u, int32_t *accept_len, int32_t *next_token)
+{
+    if (B < 1 || k < 0 || V < 1 || V > (1 << 20) || !zt || !u || !accept_len || !next_token ||
+        (k > 0 && (!zd || !draft)) || !(inv_temp > 0.0f))
+        return -1;
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        uint64_t *Ep = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
+        uint64_t *Eq = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
+        const float *ub = u + (int64_t)b * (k + 1);
+        const size_t es = dtype == ORACLE_F32 ? 4 : 2;
+        uint64_t Sp = 0, Sq = 0;
+        int n = 0;
+        for (int j = 0; j < k; ++j) {
+            const int x = draft[(int64_t)b * k + j];
+            if (x < 0 || x >= V) {
+                status = -1;
+                break;
+            }
+            Sp = oracle_logit_weights(V, (const char *)zt + ((int64_t)b * (k + 1) + j) * V * es, dtype, inv_temp, Ep);
+            Sq = oracle_logit_weights(V, (const char *)zd + ((int64_t)b * k + j) * V * es, dtype, inv_temp, Eq);
+            const u128 U = (u128)(uint32_t)(ub[j] * 16777216.0f);
+            if (U * Eq[x] * Sp < ((u128)1 << 24) * Ep[x] * Sq)
+                ++n;
+            else
+                break; /* Ep, Eq, Sp, Sq now hold the rows of the rejected position n */
+        }
+        accept_len[b] = n;
+        int have_q = n < k;
+        if (!have_q) /* all accepted: the bonus row */
+            Sp = oracle_logit_weights(V, (const char *)zt + ((int64_t)b * (k + 1) + k) * V * es, dtype, inv_temp, Ep);
+        u128 Z = 0;
+        if (have_q) {
+            for (int v = 0; v < V; ++v) {
+                const u128 a = (u128)Ep[v] * Sq, c = (u128)Eq[v] * Sp;
+                Z += a > c ? a - c : 0;
+            }
+            if (Z == 0)
+                have_q = 0; /* identical rows: fall back to the target row */
+        }
+        if (!have_q)
+            Z = Sp;
+        uint32_t m24 = (uint32_t)(ub[k] * 16777216.0f);
+        const u128 T = ((u128)m24 * Z) >> 24;
+        u128 run = 0;
+        int tok = -1;
+        for (int v = 0; v < V; ++v) {
+            if (have_q) {
+                const u128 a = (u128)Ep[v] * Sq, c = (u128)Eq[v] * Sp;
+                run += a > c ? a - c : 0;
+            } else {
+                run += Ep[v];
+            }
+            if (run > T) {
+                tok = v;
+                break;
+            }
+        }
+        next_token[b] = tok;
+        free(Ep);
+        free(Eq);
+    }
+    return status;
+}
+
+/* =====================================================================================
+ * Widening 2: confidence-based aggregation (Section "Different Aggregation Strategies"):
+ * every branch's answer is weighted by the minimum or the average of its confidence scores,
+ * then either the single most confident answer wins ("max") or the weights of identical
+ * answers are added and the largest total wins ("vote").
+ *   answers [N][B]; conf [N][B][T] in [0, 1]; conf_len [N][B] valid scores per branch (NULL: T)
+ *   weight_mode 0 = min, 1 = avg;  select_mode 0 = max, 1 = vote
+ * Branches with id < 0 or without scores do not take part.  Scores are quantised to 2^-30
+ * (trunc(c * 2^30)) so that sums are integers: min weight = q_min / 2^30, avg weight =
+ * (sum q) / (len * 2^30), both formed in fp64 and rounded once to fp32.  "vote" adds the fp32
+ * weights of identical answers in branch order.  Ties go to the earliest branch / earliest
+ * first occurrence.  winner = -1, score = 0 if nobody takes part.
+ * ===================================================================================== */
+int oracle_confidence_vote(int N, int B, int T, const int32_t *answers, const float *conf, const int32_t *conf_len,
+                           int weight_mode, int select_mode, int32_t *winner, float *winner_score)
+{
+    if (N < 1 || B < 1 || T < 1 || !answers || !conf || !winner || !winner_score || weight_mode < 0 ||
+        weight_mode > 1 || select_mode < 0 || select_mode > 1)
+        return -1;
+    for (int n = 0; n < N; ++n) {
+        float *w = (float *)malloc(sizeof(float) * (size_t)B);
+        int *ok = (int *)malloc(sizeof(int) * (size_t)B);
+        for (int b = 0; b < B; ++b) {
+            int len = conf_len ? conf_len[(int64_t)n * B + b] : T;
+            if (len > T)
+                len = T;
+            ok[b] = answers[(int64_t)n * B + b] >= 0 && len > 0;
+            w[b] = 0.0f;
+            if (!ok[b])
+                continue;
+            const float *c = conf + ((int64_t)n * B + b) * T;
+            uint64_t sum = 0, mn = UINT64_MAX;
+            for (int t = 0; t < len; ++t) {
+                const uint64_t q = (uint64_t)(c[t] * 1073741824.0f); /* trunc(c * 2^30) */
+                sum += q;
+                if (q < mn)
+                    mn = q;
+            }
+            w[b] = weight_mode == 0 ? (float)((double)mn / 1073741824.0)
+                                    : (float)((double)sum / ((double)len * 1073741824.0));
+        }
+        int32_t best = -1;
+        float best_score = 0.0f;
+        int have = 0;
+        const int32_t *a = answers + (int64_t)n * B;
+        for (int i = 0; i < B; ++i) {
+            if (!ok[i])
+                continue;
+            float score;
+            if (select_mode == 0) {
+                score = w[i];
+            } else {
+                int first = 1;
+                for (int j = 0; j < i; ++j)
+                    if (ok[j] && a[j] == a[i])
+                        first = 0;
+                if (!first)
+                    continue;
+                score = 0.0f;
+                for (int j = 0; j < B; ++j)
+                    if (ok[j] && a[j] == a[i])
+                        score = score + w[j];
+            }
+            if (!have || score > best_score) {
+                have = 1;
+                best = a[i];
+                best_score = score;
+            }
+        }
+        winner[n] = best;
+        winner_score[n] = have ? best_score : 0.0f;
+        free(w);
+        free(ok);
+    }
+    return 0;
+}

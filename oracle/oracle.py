@@ -37,6 +37,12 @@ def _load():
         lib.oracle_spec_accept.argtypes = [c_int] * 3 + [vp] * 6
         lib.oracle_majority_vote.restype = c_int
         lib.oracle_majority_vote.argtypes = [c_int] * 2 + [vp] * 3
+        lib.oracle_logit_weights.restype = ctypes.c_uint64
+        lib.oracle_logit_weights.argtypes = [c_int, vp, c_int, ctypes.c_float, vp]
+        lib.oracle_spec_accept_logits.restype = c_int
+        lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 4
+        lib.oracle_confidence_vote.restype = c_int
+        lib.oracle_confidence_vote.argtypes = [c_int] * 3 + [vp] * 3 + [c_int] * 2 + [vp] * 2
         _lib = lib
     return _lib
 
@@ -121,3 +127,49 @@ def majority_vote(answers):
     if rc != 0:
         raise ValueError("oracle_majority_vote rejected the call (rc=%d)" % rc)
     return w, c
+
+
+def logit_weights(z_row, inv_temp: float = 1.0):
+    """Integer softmax weights of one row of logits: (E [V] uint64, S)."""
+    z, dt = _kv(np.ascontiguousarray(z_row))
+    E = np.empty((z.shape[0],), dtype=np.uint64)
+    S = _load().oracle_logit_weights(z.shape[0], _ptr(z), dt, float(inv_temp), _ptr(E))
+    return E, int(S)
+
+
+def spec_accept_logits(zt, zd, draft, u, inv_temp: float = 1.0):
+    """Acceptance from target logits zt [B][k+1][V] and draft logits zd [B][k][V] (float32 or uint16 = bf16
+    bit patterns).  Returns (accept_len [B], next_token [B])."""
+    zt, dt = _kv(zt)
+    B, R, V = zt.shape
+    k = R - 1
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    if k > 0:
+        zd, dt2 = _kv(zd)
+        assert dt2 == dt and zd.shape == (B, k, V)
+        draft = np.ascontiguousarray(draft, dtype=np.int32)
+    else:
+        zd, draft = None, None
+    n = np.empty((B,), dtype=np.int32)
+    t = np.empty((B,), dtype=np.int32)
+    rc = _load().oracle_spec_accept_logits(B, k, V, _ptr(zt), _ptr(zd), dt, float(inv_temp), _ptr(draft), _ptr(u),
+                                           _ptr(n), _ptr(t))
+    if rc != 0:
+        raise ValueError("oracle_spec_accept_logits rejected the call (rc=%d)" % rc)
+    return n, t
+
+
+def confidence_vote(answers, conf, conf_len=None, weight_mode: str = "avg", select_mode: str = "vote"):
+    """answers [N][B] int32, conf [N][B][T] float32 -> (winner [N] int32, score [N] float32)."""
+    a = np.ascontiguousarray(answers, dtype=np.int32)
+    c = np.ascontiguousarray(conf, dtype=np.float32)
+    N, B, T = c.shape
+    assert a.shape == (N, B)
+    cl = None if conf_len is None else np.ascontiguousarray(conf_len, dtype=np.int32)
+    w = np.empty((N,), dtype=np.int32)
+    s = np.empty((N,), dtype=np.float32)
+    rc = _load().oracle_confidence_vote(N, B, T, _ptr(a), _ptr(c), _ptr(cl), {"min": 0, "avg": 1}[weight_mode],
+                                        {"max": 0, "vote": 1}[select_mode], _ptr(w), _ptr(s))
+    if rc != 0:
+        raise ValueError("oracle_confidence_vote rejected the call (rc=%d)" % rc)
+    return w, s
