@@ -120,6 +120,39 @@ int spec_accept(int32_t B, int32_t k, int32_t V, const float *p, const float *q,
                 const float *u, int32_t *accept_len, int32_t *next_token, void *workspace,
                 size_t workspace_bytes, void *stream);
 
+/* Bytes of workspace spec_accept_logits needs (0 if the sizes are invalid). */
+size_t spec_accept_logits_workspace_bytes(int32_t B, int32_t k, int32_t V);
+
+/*
+ * spec_accept_logits -- the same acceptance rule as spec_accept, taken straight from the target
+ * and draft LOGITS (Section 2: the draft model proposes, the target model verifies), so the
+ * V-wide softmax outputs never go through memory.  The distributions are
+ * softmax(z * inv_temperature), defined on integers so that the result does not depend on
+ * summation order or on an exp() implementation:
+ *   y_v = fp32(z_v) * inv_temperature, m = max_v y_v, t_v = (y_v - m) * log2(e)   (fp32, each
+ *   operation rounded once), E_v = trunc(P(frac(-t_v)) * 2^(30 - floor(-t_v))), 0 when
+ *   floor(-t_v) >= 31, where P(f) = 1 + f(c1 + f(c2 + ... + f c6)) evaluated by fused
+ *   multiply-adds approximates 2^-f on [0, 1) to 1.4e-7 with (c1..c6) = (-0x1.62e430p-1,
+ *   0x1.ebfbaap-3, -0x1.c6a66cp-5, 0x1.3a7ae4p-7, -0x1.52a284p-10, 0x1.e243bep-14);
+ *   S = sum_v E_v; the probability of token v is E_v / S exactly.
+ * Draft x_j is accepted iff U_j * Eq_j(x_j) * Sp_j < 2^24 * Ep_j(x_j) * Sq_j, U_j = trunc(u_j * 2^24)
+ * (the test u < min(1, p/q) on these rationals).  After the first rejection at n the next token
+ * is drawn with weights W_v = max(0, Ep_n(v) * Sq_n - Eq_n(v) * Sp_n) (the row Ep_n if all W are 0);
+ * if all k drafts are accepted, with weights Ep_k(v).  token = first v with
+ * W_0 + ... + W_v > floor(trunc(u[b][k] * 2^24) * sum(W) / 2^24).  All in 128-bit integers.
+ *
+ *   1 <= B <= 65535, 0 <= k <= 256, 1 <= V <= 2^20
+ *   target_logits [B][k+1][V], draft_logits [B][k][V] (NULL iff k == 0): logit_dtype = LOTTS_F32 or
+ *       LOTTS_BF16, finite or -inf; inv_temperature > 0
+ *   draft [B][k] int32 (NULL iff k == 0), u [B][k+1] fp32 in [0, 1)
+ *   accept_len [B], next_token [B] int32 out
+ *   workspace: >= spec_accept_logits_workspace_bytes(B, k, V), 16-byte aligned, any contents
+ */
+int spec_accept_logits(int32_t B, int32_t k, int32_t V, const void *target_logits, const void *draft_logits,
+                       int32_t logit_dtype, float inv_temperature, const int32_t *draft, const float *u,
+                       int32_t *accept_len, int32_t *next_token, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
 /*
  * majority_vote -- the answer most branches agree on (Section 1 and Section 4.1: branches are
  * aggregated by majority voting), for N independent questions at once.
@@ -131,6 +164,25 @@ int spec_accept(int32_t B, int32_t k, int32_t V, const float *p, const float *q,
  */
 int majority_vote(int32_t N, int32_t B, const int32_t *answers, int32_t *winner, int32_t *winner_count,
                   void *stream);
+
+/*
+ * confidence_vote -- confidence-based aggregation of the branches' answers (Section "Different
+ * Aggregation Strategies"): every branch's answer is weighted by the minimum or the average of
+ * its confidence scores; then either the single most confident answer wins ("max"), or the
+ * weights of identical answers are added and the largest total wins ("vote").
+ *
+ *   answers [N][B] int32 (id < 0: no answer), conf [N][B][T] fp32 in [0, 1],
+ *   conf_len [N][B] int32 valid scores per branch (NULL: all T)
+ *   weight_mode 0 = min, 1 = avg;  select_mode 0 = max, 1 = vote;  1 <= B <= 1024
+ *   winner [N] int32, winner_score [N] fp32 out; (-1, 0) if no branch takes part
+ * Scores are quantised to trunc(c * 2^30) so that sums are integers; a branch's weight is
+ * q_min / 2^30 or sum(q) / (len * 2^30), formed in fp64 and rounded once to fp32; "vote" adds the
+ * fp32 weights of identical answers in branch order; ties go to the earliest branch (max) or the
+ * earliest first occurrence (vote).  Branches without an answer or without scores are left out.
+ */
+int confidence_vote(int32_t N, int32_t B, int32_t T, const int32_t *answers, const float *conf,
+                    const int32_t *conf_len, int32_t weight_mode, int32_t select_mode, int32_t *winner,
+                    float *winner_score, void *stream);
 
 #ifdef __cplusplus
 }

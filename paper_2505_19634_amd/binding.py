@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "liblotts.so")
 LOTTS_F32, LOTTS_BF16 = 0, 1
 
 EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
-           "spec_accept_workspace_bytes", "spec_accept", "majority_vote")
+           "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
+           "majority_vote", "confidence_vote")
 
 
 class AttnDesc(ctypes.Structure):
@@ -61,6 +62,12 @@ def load() -> ctypes.CDLL:
         lib.spec_accept.argtypes = [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
         lib.majority_vote.restype = ctypes.c_int
         lib.majority_vote.argtypes = [i32, i32, vp, vp, vp, vp]
+        lib.spec_accept_logits_workspace_bytes.restype = sz
+        lib.spec_accept_logits_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.spec_accept_logits.restype = ctypes.c_int
+        lib.spec_accept_logits.argtypes = [i32, i32, i32, vp, vp, i32, ctypes.c_float] + [vp] * 4 + [vp, sz, vp]
+        lib.confidence_vote.restype = ctypes.c_int
+        lib.confidence_vote.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -206,3 +213,68 @@ def majority_vote(answers: torch.Tensor, *, winner: Optional[torch.Tensor] = Non
     if rc != 0:
         raise LottsError(rc, "majority_vote")
     return winner, winner_count
+
+
+def spec_accept_logits(target_logits: torch.Tensor, draft_logits: Optional[torch.Tensor], draft: Optional[torch.Tensor],
+                       u: torch.Tensor, *, inv_temperature: float = 1.0, accept_len: Optional[torch.Tensor] = None,
+                       next_token: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """target_logits [B][k+1][V], draft_logits [B][k][V] (both bfloat16 or both float32, contiguous), draft [B][k]
+    int32, u [B][k+1] fp32, on the GPU.  Returns (accept_len [B] int32, next_token [B] int32)."""
+    lib = load()
+    if not target_logits.is_cuda:
+        raise ValueError("spec_accept_logits runs on the GPU only")
+    B, R, V = target_logits.shape
+    k = R - 1
+    if target_logits.dtype == torch.bfloat16:
+        dt = LOTTS_BF16
+    elif target_logits.dtype == torch.float32:
+        dt = LOTTS_F32
+    else:
+        raise TypeError("logits must be bfloat16 or float32")
+    if not target_logits.is_contiguous() or u.dtype != torch.float32 or not u.is_contiguous() or tuple(u.shape) != (B, R):
+        raise TypeError("target_logits must be contiguous and u contiguous float32 [B][k+1]")
+    if k > 0:
+        if (draft_logits is None or draft is None or draft_logits.dtype != target_logits.dtype or
+                tuple(draft_logits.shape) != (B, k, V) or not draft_logits.is_contiguous() or
+                draft.dtype != torch.int32 or tuple(draft.shape) != (B, k) or not draft.is_contiguous()):
+            raise TypeError("draft_logits must be [B][k][V] of the same dtype, draft [B][k] int32, both contiguous")
+    else:
+        draft_logits, draft = None, None
+    if accept_len is None:
+        accept_len = torch.empty((B,), dtype=torch.int32, device=u.device)
+    if next_token is None:
+        next_token = torch.empty((B,), dtype=torch.int32, device=u.device)
+    need = lib.spec_accept_logits_workspace_bytes(B, k, V)
+    if need == 0:
+        raise LottsError(-2, "spec_accept_logits_workspace_bytes")
+    ws = _workspace("accept_logits", u.device, need) if workspace is None else workspace
+    rc = lib.spec_accept_logits(B, k, V, _ptr(target_logits), _ptr(draft_logits), dt, float(inv_temperature), _ptr(draft),
+                                _ptr(u), _ptr(accept_len), _ptr(next_token), _ptr(ws), ws.numel() * ws.element_size(),
+                                _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "spec_accept_logits")
+    return accept_len, next_token
+
+
+def confidence_vote(answers: torch.Tensor, conf: torch.Tensor, conf_len: Optional[torch.Tensor] = None, *,
+                    weight_mode: str = "avg", select_mode: str = "vote", stream: Optional[torch.cuda.Stream] = None):
+    """answers [N][B] int32, conf [N][B][T] fp32, conf_len [N][B] int32 or None, on the GPU.
+    Returns (winner [N] int32, winner_score [N] fp32)."""
+    lib = load()
+    if not answers.is_cuda:
+        raise ValueError("confidence_vote runs on the GPU only")
+    N, B, T = conf.shape
+    if (answers.dtype != torch.int32 or tuple(answers.shape) != (N, B) or not answers.is_contiguous() or
+            conf.dtype != torch.float32 or not conf.is_contiguous()):
+        raise TypeError("answers must be contiguous int32 [N][B], conf contiguous float32 [N][B][T]")
+    if conf_len is not None and (conf_len.dtype != torch.int32 or tuple(conf_len.shape) != (N, B) or
+                                 not conf_len.is_contiguous()):
+        raise TypeError("conf_len must be contiguous int32 [N][B]")
+    winner = torch.empty((N,), dtype=torch.int32, device=answers.device)
+    score = torch.empty((N,), dtype=torch.float32, device=answers.device)
+    rc = lib.confidence_vote(N, B, T, _ptr(answers), _ptr(conf), _ptr(conf_len), {"min": 0, "avg": 1}[weight_mode],
+                             {"max": 0, "vote": 1}[select_mode], _ptr(winner), _ptr(score), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "confidence_vote")
+    return winner, score

@@ -9,7 +9,8 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblotts.so")
 CALIB = os.path.join(_HERE, "calib_copy")
-SOURCES = ["verify_attention.hip", "spec_accept.hip", "majority_vote.hip"]
+SOURCES = ["verify_attention.hip", "spec_accept.hip", "spec_accept_logits.hip", "majority_vote.hip",
+           "confidence_vote.hip"]
 
 
 def build(verbose: bool = False) -> str:

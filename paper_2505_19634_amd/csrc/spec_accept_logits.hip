@@ -1,0 +1,427 @@
+// spec_accept_logits: speculative-sampling acceptance straight from target / draft LOGITS, so
+// that the V-wide softmax outputs p and q are never written to memory (for the 32B-shaped
+// workload: 34 MB of bf16 logits read instead of 34 MB read + 68 MB written + 13-19 MB re-read).
+// The rule is the one of spec_accept (paper Section 2 / 3.2: draft proposes, target verifies,
+// losslessly); the distributions are softmax(z * inv_temperature).
+//
+// To be independent of summation order and of any exp() implementation, the softmax is defined on
+// integers: y_v = fp32(z_v) * inv_temp, m = max_v y_v, t_v = (y_v - m) * log2(e),
+//   E_v = trunc(P(frac(-t_v)) * 2^(30 - floor(-t_v)))   (0 when floor(-t_v) >= 31),
+// P a fixed degree-6 polynomial for 2^-f evaluated with fused multiply-adds, S = sum_v E_v, and the
+// probability of v is E_v / S exactly.  Accept x iff U * Eq(x) * Sp < 2^24 * Ep(x) * Sq with
+// U = trunc(u * 2^24); residual weights W_v = max(0, Ep_v * Sq - Eq_v * Sp); bonus weights Ep_v;
+// token = first v whose prefix sum exceeds floor(U_k * sum W / 2^24).  128-bit integers.
+//
+// Three launches:
+//   lg_rowstats_kernel  one 1024-thread workgroup per logit row (B * (2k + 1) rows): row maximum,
+//                       then S; the second sweep of the row is served by the L2.
+//   lg_scan_kernel      grid (chunks, B): accept tests -> n; 128-bit chunk sums of the weights of row n.
+//   lg_pick_kernel      grid (B): chunk and token where the integer CDF crosses the threshold.
+#include "lotts_common.h"
+
+namespace lotts {
+
+typedef unsigned __int128 u128;
+
+constexpr int kLgThreads = 256;
+constexpr int kLgWaves = kLgThreads / kWave;
+constexpr int kLgStatThreads = 1024;
+constexpr int kLgChunk = 2048;       // tokens per chunk: 8 per thread
+constexpr int kLgMaxChunks = 512;    // V <= 2^20
+constexpr int kLgMaxK = kLgThreads;
+
+struct RowStat {
+    float m;          // row maximum of y
+    float pad;
+    unsigned long long S;  // sum of the integer weights
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+
+// 2^-f on [0, 1): the polynomial of the definition (c0 = 1 exactly), fused multiply-adds only
+__device__ __forceinline__ float pow2_neg_poly(float f) {
+    float g = 0x1.e243bep-14f;
+    g = __fmaf_rn(g, f, -0x1.52a284p-10f);
+    g = __fmaf_rn(g, f, 0x1.3a7ae4p-7f);
+    g = __fmaf_rn(g, f, -0x1.c6a66cp-5f);
+    g = __fmaf_rn(g, f, 0x1.ebfbaap-3f);
+    g = __fmaf_rn(g, f, -0x1.62e430p-1f);
+    g = __fmaf_rn(g, f, 1.0f);
+    return g;
+}
+
+// E = trunc(2^t * 2^30) through the definition's steps; every operation individually rounded
+__device__ __forceinline__ unsigned long long logit_weight(float y, float m) {
+    const float t = __fmul_rn(__fsub_rn(y, m), 0x1.715476p+0f);
+    const float a = -t;
+    const float nf = floorf(a);
+    if (!(nf < 31.0f)) return 0ull;
+    const float f = __fsub_rn(a, nf);
+    const float g = pow2_neg_poly(f);
+    const float scale = __uint_as_float((unsigned)(127 + 30 - (int)nf) << 23);  // 2^(30 - n), exact
+    return __float2ull_rz(__fmul_rn(g, scale));
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_y(const void* z, size_t idx, float inv_temp) {
+    const float v = BF16 ? bf16_bits_to_float(static_cast<const unsigned short*>(z)[idx])
+                         : static_cast<const float*>(z)[idx];
+    return __fmul_rn(v, inv_temp);
+}
+
+// 8 consecutive logits starting at a multiple of 8 (rows are 16-byte aligned when V % 8 == 0)
+template <bool BF16>
+__device__ __forceinline__ void load_y8(const void* z, size_t idx, float inv_temp, float (&y)[8]) {
+    if (BF16) {
+        const uint4 r = *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(z) + idx);
+        const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            y[2 * i] = __fmul_rn(__uint_as_float(w[i] << 16), inv_temp);
+            y[2 * i + 1] = __fmul_rn(__uint_as_float(w[i] & 0xffff0000u), inv_temp);
+        }
+    } else {
+        const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + idx);
+        const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + idx + 4);
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = __fmul_rn(v[i], inv_temp);
+    }
+}
+
+__device__ __forceinline__ u128 shfl_down_u128(u128 v, int d) {
+    const unsigned long long lo = shfl_down_u64((unsigned long long)v, d);
+    const unsigned long long hi = shfl_down_u64((unsigned long long)(v >> 64), d);
+    return ((u128)hi << 64) | lo;
+}
+__device__ __forceinline__ u128 shfl_up_u128(u128 v, int d) {
+    const unsigned long long lo = shfl_up_u64((unsigned long long)v, d);
+    const unsigned long long hi = shfl_up_u64((unsigned long long)(v >> 64), d);
+    return ((u128)hi << 64) | lo;
+}
+
+// sum over a 256-thread workgroup, result in every thread
+__device__ __forceinline__ u128 block_sum_u128(u128 v, u128* sh /*[kLgWaves]*/) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += shfl_down_u128(v, d);
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if ((tid & (kWave - 1)) == 0) sh[tid / kWave] = v;
+    __syncthreads();
+    u128 s = 0;
+#pragma unroll
+    for (int w = 0; w < kLgWaves; ++w) s += sh[w];
+    return s;
+}
+// exclusive prefix sum in thread order over a 256-thread workgroup
+__device__ __forceinline__ u128 block_excl_scan_u128(u128 v, u128* sh /*[kLgWaves]*/) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+    u128 incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const u128 o = shfl_up_u128(incl, d);
+        if (lane >= d) incl += o;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) sh[w] = incl;
+    __syncthreads();
+    u128 base = 0;
+#pragma unroll
+    for (int i = 0; i < kLgWaves; ++i) base += (i < w) ? sh[i] : (u128)0;
+    return base + incl - v;
+}
+
+// row index of target row (b, j) and of draft row (b, j) in the stats array
+__device__ __forceinline__ int trow(int b, int j, int k) { return b * (k + 1) + j; }
+__device__ __forceinline__ int drow(int B, int b, int j, int k) { return B * (k + 1) + b * k + j; }
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kLgStatThreads) void lg_rowstats_kernel(int B, int k, int V, const void* __restrict__ zt,
+                                                                     const void* __restrict__ zd, float inv_temp,
+                                                                     RowStat* __restrict__ stats) {
+    __shared__ float sh_m[kLgStatThreads / kWave];
+    __shared__ unsigned long long sh_s[kLgStatThreads / kWave];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const int nt = B * (k + 1);
+    const void* z = r < nt ? zt : zd;
+    const size_t base = (size_t)(r < nt ? r : r - nt) * V;
+    // sweep 1: maximum
+    float m = -INFINITY;
+    if (VEC) {
+        for (int i = tid * 8; i < V; i += kLgStatThreads * 8) {
+            float y[8];
+            load_y8<BF16>(z, base + i, inv_temp, y);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m = fmaxf(m, y[e]);
+        }
+    } else {
+        for (int i = tid; i < V; i += kLgStatThreads) m = fmaxf(m, load_y<BF16>(z, base + i, inv_temp));
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, kWave));
+    if ((tid & (kWave - 1)) == 0) sh_m[tid / kWave] = m;
+    __syncthreads();
+    m = sh_m[0];
+#pragma unroll
+    for (int w = 1; w < kLgStatThreads / kWave; ++w) m = fmaxf(m, sh_m[w]);
+    // sweep 2: sum of the integer weights
+    unsigned long long s = 0;
+    if (VEC) {
+        for (int i = tid * 8; i < V; i += kLgStatThreads * 8) {
+            float y[8];
+            load_y8<BF16>(z, base + i, inv_temp, y);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += logit_weight(y[e], m);
+        }
+    } else {
+        for (int i = tid; i < V; i += kLgStatThreads) s += logit_weight(load_y<BF16>(z, base + i, inv_temp), m);
+    }
+    s = wave_sum_u64(s);
+    if ((tid & (kWave - 1)) == 0) sh_s[tid / kWave] = s;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long tot = 0;
+        for (int w = 0; w < kLgStatThreads / kWave; ++w) tot += sh_s[w];
+        stats[r].m = m;
+        stats[r].pad = 0.f;
+        stats[r].S = tot;
+    }
+}
+
+// accepted length of branch b; every thread of the 256-thread workgroup gets it
+template <bool BF16>
+__device__ __forceinline__ int lg_accepted_length(int B, int b, int k, int V, const void* zt, const void* zd,
+                                                  float inv_temp, const int32_t* draft, const float* u,
+                                                  const RowStat* stats, int* sh_first) {
+    const int tid = threadIdx.x;
+    bool rejected = false;
+    if (tid < k) {
+        int x = draft[(size_t)b * k + tid];
+        x = x < 0 ? 0 : (x >= V ? V - 1 : x);
+        const RowStat sp = stats[trow(b, tid, k)], sq = stats[drow(B, b, tid, k)];
+        const unsigned long long Ep = logit_weight(load_y<BF16>(zt, (size_t)trow(b, tid, k) * V + x, inv_temp), sp.m);
+        const unsigned long long Eq = logit_weight(load_y<BF16>(zd, ((size_t)b * k + tid) * V + x, inv_temp), sq.m);
+        const u128 U = (u128)(unsigned)(u[(size_t)b * (k + 1) + tid] * 16777216.0f);
+        rejected = !(U * Eq * sp.S < ((u128)1 << 24) * Ep * sq.S);
+    }
+    const unsigned long long mask = __ballot(rejected);
+    if ((tid & (kWave - 1)) == 0) sh_first[tid / kWave] = mask ? (tid + __ffsll((long long)mask) - 1) : k;
+    __syncthreads();
+    int n = k;
+#pragma unroll
+    for (int w = 0; w < kLgWaves; ++w) n = sh_first[w] < n ? sh_first[w] : n;
+    return n;
+}
+
+// the 8 weights a thread owns in a chunk (tokens lo .. lo+7, clipped to V): residual or plain
+template <bool BF16, bool VEC>
+__device__ __forceinline__ void lg_weights8(const void* zt_row, const void* zd_row, int lo, int V, float inv_temp,
+                                            bool residual, RowStat sp, RowStat sq, u128 (&W)[8],
+                                            unsigned long long (&Ep)[8]) {
+    float yp[8], yq[8];
+    if (VEC && lo + 8 <= V) {
+        load_y8<BF16>(zt_row, lo, inv_temp, yp);
+        if (residual) load_y8<BF16>(zd_row, lo, inv_temp, yq);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool in = lo + e < V;
+            yp[e] = in ? load_y<BF16>(zt_row, lo + e, inv_temp) : -INFINITY;
+            yq[e] = (in && residual) ? load_y<BF16>(zd_row, lo + e, inv_temp) : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool in = lo + e < V;
+        Ep[e] = in ? logit_weight(yp[e], sp.m) : 0ull;
+        if (residual) {
+            const unsigned long long Eq = in ? logit_weight(yq[e], sq.m) : 0ull;
+            const u128 a = (u128)Ep[e] * sq.S, c = (u128)Eq * sp.S;
+            W[e] = a > c ? a - c : (u128)0;
+        } else {
+            W[e] = Ep[e];
+        }
+    }
+}
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kLgThreads) void lg_scan_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
+                                                             const void* __restrict__ zd, float inv_temp,
+                                                             const int32_t* __restrict__ draft,
+                                                             const float* __restrict__ u,
+                                                             const RowStat* __restrict__ stats,
+                                                             int32_t* __restrict__ accept_len, u128* __restrict__ wsum,
+                                                             unsigned long long* __restrict__ psum) {
+    __shared__ int sh_first[kLgWaves];
+    __shared__ u128 sh_w[kLgWaves];
+    const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, stats, sh_first);
+    if (c == 0 && tid == 0) accept_len[b] = n;
+    const bool residual = n < k;
+    const size_t es = BF16 ? 2 : 4;
+    const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
+    const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
+    const RowStat sp = stats[trow(b, n, k)];
+    const RowStat sq = residual ? stats[drow(B, b, n, k)] : sp;
+    u128 W[8];
+    unsigned long long Ep[8];
+    lg_weights8<BF16, VEC>(zt_row, zd_row, c * kLgChunk + tid * 8, V, inv_temp, residual, sp, sq, W, Ep);
+    u128 w = 0, e = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        w += W[i];
+        e += Ep[i];
+    }
+    w = block_sum_u128(w, sh_w);
+    e = block_sum_u128(e, sh_w);
+    if (tid == 0) {
+        wsum[(size_t)b * nchunks + c] = w;
+        psum[(size_t)b * nchunks + c] = (unsigned long long)e;
+    }
+}
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
+                                                             const void* __restrict__ zd, float inv_temp,
+                                                             const float* __restrict__ u,
+                                                             const RowStat* __restrict__ stats,
+                                                             const int32_t* __restrict__ accept_len,
+                                                             const u128* __restrict__ wsum,
+                                                             const unsigned long long* __restrict__ psum,
+                                                             int32_t* __restrict__ next_token) {
+    __shared__ u128 sh_w[kLgWaves];
+    __shared__ u128 sh_base;
+    __shared__ int sh_chunk;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n = accept_len[b];
+    // kLgMaxChunks = 2 * kLgThreads: every thread owns two consecutive chunk sums
+    const int c0 = tid * 2;
+    u128 w0 = 0, w1 = 0;
+    unsigned long long p0 = 0, p1 = 0;
+    if (c0 < nchunks) {
+        w0 = wsum[(size_t)b * nchunks + c0];
+        p0 = psum[(size_t)b * nchunks + c0];
+    }
+    if (c0 + 1 < nchunks) {
+        w1 = wsum[(size_t)b * nchunks + c0 + 1];
+        p1 = psum[(size_t)b * nchunks + c0 + 1];
+    }
+    u128 Z = block_sum_u128(w0 + w1, sh_w);
+    bool residual = n < k;
+    if (residual && Z == 0) {  // empty residual: sample the target row itself (uniform branch: n and Z are)
+        residual = false;
+        w0 = p0;
+        w1 = p1;
+        Z = block_sum_u128(w0 + w1, sh_w);
+    }
+    unsigned m24 = (unsigned)(u[(size_t)b * (k + 1) + k] * 16777216.0f);
+    m24 = m24 > 16777215u ? 16777215u : m24;  // u must be < 1; keeps T < Z regardless
+    const u128 T = ((u128)m24 * Z) >> 24;
+    u128 excl = block_excl_scan_u128(w0 + w1, sh_w);
+    if (excl <= T && T < excl + w0 + w1) {  // exactly one thread: T < Z and Z > 0 (the row maximum weighs 2^30)
+        const bool second = !(T < excl + w0);
+        sh_chunk = c0 + (second ? 1 : 0);
+        sh_base = second ? excl + w0 : excl;
+    }
+    __syncthreads();
+    const int c = sh_chunk;
+    const u128 base = sh_base;
+    const size_t es = BF16 ? 2 : 4;
+    const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
+    const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
+    const RowStat sp = stats[trow(b, n, k)];
+    const RowStat sq = residual ? stats[drow(B, b, n, k)] : sp;
+    u128 W[8];
+    unsigned long long Ep[8];
+    const int lo = c * kLgChunk + tid * 8;
+    lg_weights8<BF16, VEC>(zt_row, zd_row, lo, V, inv_temp, residual, sp, sq, W, Ep);
+    u128 local = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) local += W[i];
+    const u128 run = base + block_excl_scan_u128(local, sh_w);
+    if (run <= T && T < run + local) {
+        int tok = lo;
+#pragma unroll
+        for (int i = 7; i >= 0; --i) {  // the first i whose inclusive prefix exceeds T
+            u128 pre = run;
+#pragma unroll
+            for (int j = 0; j <= i; ++j) pre += W[j];
+            if (pre > T) tok = lo + i;
+        }
+        next_token[b] = tok;
+    }
+}
+
+struct LgLayout {
+    size_t off_stats, off_wsum, off_psum, total;
+    int nchunks;
+};
+static inline LgLayout lg_layout(int B, int k, int V) {
+    LgLayout l;
+    l.nchunks = (V + kLgChunk - 1) / kLgChunk;
+    const size_t rows = (size_t)B * (2 * k + 1);
+    l.off_stats = 0;
+    l.off_wsum = (rows * sizeof(RowStat) + 255) & ~(size_t)255;
+    l.off_psum = l.off_wsum + (((size_t)B * l.nchunks * sizeof(u128) + 255) & ~(size_t)255);
+    l.total = l.off_psum + (((size_t)B * l.nchunks * sizeof(unsigned long long) + 255) & ~(size_t)255);
+    return l;
+}
+static inline bool lg_sizes_ok(int B, int k, int V) {
+    return B >= 1 && B <= 65535 && k >= 0 && k <= kLgMaxK && V >= 1 && V <= (1 << 20);
+}
+
+template <bool BF16, bool VEC>
+static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float inv_temp, const int32_t* draft,
+                     const float* u, int32_t* accept_len, int32_t* next_token, void* workspace, hipStream_t s) {
+    const LgLayout l = lg_layout(B, k, V);
+    RowStat* stats = reinterpret_cast<RowStat*>(static_cast<char*>(workspace) + l.off_stats);
+    u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
+    unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
+    hipLaunchKernelGGL((lg_rowstats_kernel<BF16, VEC>), dim3(B * (2 * k + 1)), dim3(kLgStatThreads), 0, s, B, k, V, zt, zd,
+                       inv_temp, stats);
+    int rc = check_launch();
+    if (rc != LOTTS_OK) return rc;
+    hipLaunchKernelGGL((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd,
+                       inv_temp, draft, u, stats, accept_len, wsum, psum);
+    rc = check_launch();
+    if (rc != LOTTS_OK) return rc;
+    hipLaunchKernelGGL((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
+                       stats, accept_len, wsum, psum, next_token);
+    return check_launch();
+}
+
+}  // namespace lotts
+
+extern "C" size_t spec_accept_logits_workspace_bytes(int32_t B, int32_t k, int32_t V) {
+    if (!lotts::lg_sizes_ok(B, k, V)) return 0;
+    return lotts::lg_layout(B, k, V).total;
+}
+
+extern "C" int spec_accept_logits(int32_t B, int32_t k, int32_t V, const void* target_logits, const void* draft_logits,
+                                  int32_t logit_dtype, float inv_temperature, const int32_t* draft, const float* u,
+                                  int32_t* accept_len, int32_t* next_token, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    using namespace lotts;
+    if (!lg_sizes_ok(B, k, V)) return LOTTS_ERR_SHAPE;
+    if (logit_dtype != LOTTS_F32 && logit_dtype != LOTTS_BF16) return LOTTS_ERR_DTYPE;
+    if (!(inv_temperature > 0.0f) || inv_temperature > 3.0e38f) return LOTTS_ERR_SHAPE;
+    if (!target_logits || !u || !accept_len || !next_token || !workspace) return LOTTS_ERR_NULL;
+    if (k > 0 && (!draft_logits || !draft)) return LOTTS_ERR_NULL;
+    if (workspace_bytes < spec_accept_logits_workspace_bytes(B, k, V)) return LOTTS_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return LOTTS_ERR_SHAPE;
+    const bool bf16 = logit_dtype == LOTTS_BF16;
+    const uintptr_t es = bf16 ? 2 : 4;
+    if (((uintptr_t)target_logits | (uintptr_t)draft_logits) & (es - 1)) return LOTTS_ERR_SHAPE;
+    // 8-wide loads need every row start 16-byte (bf16) / 32-byte-run (fp32: two 16-byte loads) aligned
+    const bool vec = (V % 8 == 0) && ((((uintptr_t)target_logits | (uintptr_t)draft_logits) & 15) == 0);
+    hipStream_t s = (hipStream_t)stream;
+    if (bf16)
+        return vec ? lg_launch<true, true>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
+                                           next_token, workspace, s)
+                   : lg_launch<true, false>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
+                                            next_token, workspace, s);
+    return vec ? lg_launch<false, true>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
+                                        next_token, workspace, s)
+               : lg_launch<false, false>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
+                                         next_token, workspace, s);
+}

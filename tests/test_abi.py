@@ -11,10 +11,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module")
 def lib():
+    if not os.path.exists(os.path.join(ROOT, "paper_2505_19634_amd", "liblotts.so")):
+        import __graft_entry__
+        __graft_entry__.build()
     from paper_2505_19634_amd import binding
-    if not os.path.exists(binding.LIB_PATH):
-        from paper_2505_19634_amd import build
-        build.build()
     return binding.load()
 
 

@@ -243,3 +243,82 @@ def test_vote_ties_go_to_first_occurrence(lotts, oracle):
     assert w.cpu().tolist() == [4, 9, 1, 3] and c.cpu().tolist() == [2, 2, 1, 2]
     w_ref, c_ref = oracle.majority_vote(a)
     assert w.cpu().tolist() == list(w_ref) and c.cpu().tolist() == list(c_ref)
+
+
+# ---------------------------------------------------------------------------- acceptance from logits
+def logit_inputs(cfg, noise_std, salt=0, bf16=False):
+    g = S.rng_for(cfg.number, 20, salt)
+    zt = (g.standard_normal((cfg.B, cfg.k + 1, cfg.V), dtype=np.float32) * np.float32(2.0))
+    zd = zt[:, :cfg.k] + g.standard_normal((cfg.B, cfg.k, cfg.V), dtype=np.float32) * np.float32(noise_std)
+    if bf16:
+        zt, zd = S.f32_to_bf16_bits(zt), S.f32_to_bf16_bits(zd)
+        zd_f = S.bf16_bits_to_f32(zd)
+    else:
+        zd_f = zd
+    from scipy.special import softmax
+    draft = np.zeros((cfg.B, cfg.k), np.int32)
+    for b in range(cfg.B):
+        for j in range(cfg.k):
+            c = np.cumsum(softmax(zd_f[b, j].astype(np.float64)))
+            draft[b, j] = min(int(np.searchsorted(c, g.random() * c[-1], side="right")), cfg.V - 1)
+    u = (g.integers(0, 1 << 24, (cfg.B, cfg.k + 1)) / float(1 << 24)).astype(np.float32)
+    return np.ascontiguousarray(zt), np.ascontiguousarray(zd), draft, u
+
+
+@pytest.mark.parametrize("cfg,bf16,inv_temp", [
+    (S.CONFIGS["C1"], False, 1.0),
+    (S.CONFIGS["C1"].with_(B=7, V=999, k=2), False, 0.8),          # scalar loads
+    (S.CONFIGS["C1"].with_(B=5, V=2048 * 3 + 8, k=5), True, 1.0),
+    (S.CONFIGS["C1"].with_(B=6, V=5000, k=0), True, 1.3),
+    (S.CONFIGS["C1"].with_(B=3, V=1, k=2), False, 1.0),
+    (S.CONFIGS["C2"].with_(B=33, V=20000, k=8), True, 1.0),
+    (S.CONFIGS["C5"].with_(B=16, V=40000), False, 1.0),
+    (S.CONFIGS["C3"], True, 1.0),                                  # full 32B-shaped size, bf16 logits
+    (S.CONFIGS["C3"], False, 0.7),
+], ids=lambda x: str(x) if not hasattr(x, "B") else "B%d_k%d_V%d" % (x.B, x.k, x.V))
+def test_accept_logits(lotts, oracle, cfg, bf16, inv_temp):
+    print("accept-from-logits case", cfg, bf16, inv_temp, flush=True)
+    zt, zd, draft, u = logit_inputs(cfg, cfg.noise_std or 1.0, bf16=bf16)
+    n, t = lotts.spec_accept_logits(to_dev(zt, bf16), to_dev(zd, bf16) if cfg.k else None,
+                                    to_dev(draft) if cfg.k else None, to_dev(u), inv_temperature=inv_temp)
+    torch.cuda.synchronize()
+    n_ref, t_ref = oracle.spec_accept_logits(zt, zd, draft, u, inv_temp)
+    assert np.array_equal(n.cpu().numpy(), n_ref), (n.cpu().numpy(), n_ref)
+    assert np.array_equal(t.cpu().numpy(), t_ref), (t.cpu().numpy(), t_ref)
+
+
+def test_accept_logits_degenerate(lotts, oracle):
+    V, k = 4096, 2
+    g = np.random.default_rng(9)
+    zt = g.normal(0, 2, (4, k + 1, V)).astype(np.float32)
+    zd = zt[:, :k].copy()                          # identical rows: accepted unless the token has no weight
+    zt[1, 0, 7] = zd[1, 0, 7] = -1e5               # branch 1: draft 7 weighs 0 on both sides -> rejected, empty residual
+    zt[2, 1, :] = -1e5
+    zt[2, 1, 100] = 0.0                            # branch 2: one-hot target at position 1
+    zd[3, 0, :] = -np.inf
+    zd[3, 0, 11] = 0.0                             # branch 3: -inf logits in the draft row
+    draft = np.array([[5, 6], [7, 8], [9, 10], [11, 12]], np.int32)
+    u = np.array([[0.3, 0.4, 0.5]] * 4, np.float32)
+    n, t = lotts.spec_accept_logits(to_dev(zt), to_dev(zd), to_dev(draft), to_dev(u))
+    n_ref, t_ref = oracle.spec_accept_logits(zt, zd, draft, u)
+    assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref)
+    assert n_ref[0] == 2 and n_ref[1] == 0 and n_ref[2] == 1 and t_ref[2] == 100
+
+
+# ---------------------------------------------------------------------------- confidence-weighted vote
+@pytest.mark.parametrize("N,B,T", [(1, 16, 64), (5, 16, 1000), (3, 64, 37), (2, 1, 5), (2, 1024, 3)])
+def test_confidence_vote(lotts, oracle, N, B, T):
+    cfg = S.CONFIGS["C3"].with_(B=B)
+    g = S.rng_for(3, S.T_CONF, salt=B + T)
+    answers = S.vote_inputs(cfg, N=N, salt=T)
+    answers[g.random((N, B)) < 0.1] = -1
+    conf = (0.3 + 0.7 * g.random((N, B, T))).astype(np.float32)
+    lens = g.integers(0, T + 1, (N, B)).astype(np.int32)
+    for wm in ("min", "avg"):
+        for sm in ("max", "vote"):
+            for cl in (None, lens):
+                w, s = lotts.confidence_vote(to_dev(answers), to_dev(conf), None if cl is None else to_dev(cl),
+                                             weight_mode=wm, select_mode=sm)
+                w_ref, s_ref = oracle.confidence_vote(answers, conf, cl, wm, sm)
+                assert np.array_equal(w.cpu().numpy(), w_ref), (wm, sm)
+                assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), (wm, sm)
