@@ -226,6 +226,50 @@ def main() -> int:
                         "emitted_tokens_per_s": float((n0 + 1).sum()) / (ms_per_step * 1e-3)},
     }
 
+    # ---- the widenings, outside the timed region: acceptance straight from bf16 logits (reads every
+    # logit row once instead of reading logits, writing p and q and reading them back), and the
+    # confidence-weighted aggregation
+    zsets = []
+    for i in range(nsets):
+        z = (torch.randn((cfg.B, cfg.R, cfg.V), generator=gen, device=dev) * cfg.logit_std)
+        zq = z[:, :cfg.k] + torch.randn((cfg.B, cfg.k, cfg.V), generator=gen, device=dev) * (cfg.noise_std or cfg.logit_std)
+        zsets.append((z.to(torch.bfloat16).contiguous(), zq.to(torch.bfloat16).contiguous()))
+        del z, zq
+    ws_lg_bytes = lib.spec_accept_logits_workspace_bytes(cfg.B, cfg.k, cfg.V)
+    ws_lg = torch.empty(ws_lg_bytes, dtype=torch.uint8, device=dev)
+    d0 = sets[0]
+
+    def lg_call(i):
+        zt, zd = zsets[i % nsets]
+        return lib.spec_accept_logits(cfg.B, cfg.k, cfg.V, P(zt), P(zd) if cfg.k else None, binding.LOTTS_BF16,
+                                      ctypes.c_float(1.0), P(d0["draft"]) if cfg.k else None, P(d0["u"]),
+                                      P(d0["accept_len"]), P(d0["next_token"]), P(ws_lg), ws_lg_bytes, sh)
+    for i in range(8):
+        assert lg_call(i) == 0
+    evl = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(100)]
+    for i, e in enumerate(evl):
+        e[0].record(stream)
+        lg_call(i)
+        e[1].record(stream)
+    torch.cuda.synchronize()
+    lg_ms = sum(e[0].elapsed_time(e[1]) for e in evl) / len(evl)
+    lg_bytes = cfg.B * (2 * cfg.k + 1) * cfg.V * 2
+    out["spec_accept_logits"] = {"ms": lg_ms, "algorithmic_bytes": lg_bytes, "logit_dtype": "bf16",
+                                 "GB/s": lg_bytes / (lg_ms * 1e-3) / 1e9,
+                                 "frac_of_hbm_peak": lg_bytes / (lg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    Tc = 1024
+    conf = 0.3 + 0.7 * torch.rand((1, cfg.B, Tc), generator=gen, device=dev)
+    cw = torch.empty((1,), dtype=torch.int32, device=dev)
+    cs = torch.empty((1,), dtype=torch.float32, device=dev)
+    evc = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(50)]
+    for e in evc:
+        e[0].record(stream)
+        lib.confidence_vote(1, cfg.B, Tc, P(d0["answers"]), P(conf), None, 1, 1, P(cw), P(cs), sh)
+        e[1].record(stream)
+    torch.cuda.synchronize()
+    out["confidence_vote"] = {"ms": sum(e[0].elapsed_time(e[1]) for e in evc) / len(evc), "scores_per_branch": Tc,
+                              "mode": "avg-vote"}
+
     # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
     if not args.no_cpu_baseline:
         import oracle

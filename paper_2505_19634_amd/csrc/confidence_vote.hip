@@ -19,50 +19,43 @@ __global__ __launch_bounds__(kConfThreads) void confidence_vote_kernel(int B, in
                                                                        float* __restrict__ winner_score) {
     __shared__ int32_t a[kConfMaxB];
     __shared__ float w[kConfMaxB];
-    __shared__ unsigned long long sh_sum[kConfThreads / kWave], sh_min[kConfThreads / kWave];
     __shared__ unsigned long long sh_key[kConfThreads / kWave];
     const int n = blockIdx.x, tid = threadIdx.x;
-    for (int b = tid; b < B; b += kConfThreads) a[b] = answers[(size_t)n * B + b];
-    __syncthreads();
-    // weights; a[b] = -1 marks a branch that does not take part
-    for (int b = 0; b < B; ++b) {
-        int len = conf_len ? conf_len[(size_t)n * B + b] : T;
-        len = len > T ? T : len;
-        const bool ok = a[b] >= 0 && len > 0;  // uniform over the workgroup
-        if (!ok) {
-            __syncthreads();
-            if (tid == 0) {
-                a[b] = -1;
-                w[b] = 0.f;
-            }
-            continue;
+    // weights: groups of LPB lanes (a power of two, at most one wavefront) reduce one branch's scores
+    // with shuffles; 256 / LPB branches are in flight at a time.  a[b] = -1 marks a branch left out.
+    int LPB = kWave;
+    while (LPB > 1 && (kConfThreads / LPB) < B) LPB >>= 1;
+    const int per_pass = kConfThreads / LPB;
+    const int sub = tid & (LPB - 1);
+    for (int b0 = 0; b0 < B; b0 += per_pass) {
+        const int b = b0 + tid / LPB;
+        const bool in = b < B;
+        int ans = -1, len = 0;
+        if (in) {
+            ans = answers[(size_t)n * B + b];
+            len = conf_len ? conf_len[(size_t)n * B + b] : T;
+            len = len > T ? T : len;
         }
-        const float* c = conf + ((size_t)n * B + b) * T;
         unsigned long long sum = 0, mn = ~0ull;
-        for (int t = tid; t < len; t += kConfThreads) {
-            const unsigned long long q = __float2ull_rz(c[t] * 1073741824.0f);  // trunc(c * 2^30)
-            sum += q;
-            mn = q < mn ? q : mn;
+        if (in && ans >= 0) {
+            const float* c = conf + ((size_t)n * B + b) * T;
+            for (int t = sub; t < len; t += LPB) {
+                const unsigned long long q = __float2ull_rz(c[t] * 1073741824.0f);  // trunc(c * 2^30)
+                sum += q;
+                mn = q < mn ? q : mn;
+            }
         }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            sum += shfl_down_u64(sum, d);
-            const unsigned long long o = shfl_down_u64(mn, d);
+        for (int d = LPB >> 1; d >= 1; d >>= 1) {  // xor shuffles stay inside the aligned group of LPB lanes
+            sum += shfl_u64(sum, (tid & (kWave - 1)) ^ d);
+            const unsigned long long o = shfl_u64(mn, (tid & (kWave - 1)) ^ d);
             mn = o < mn ? o : mn;
         }
-        __syncthreads();
-        if ((tid & (kWave - 1)) == 0) {
-            sh_sum[tid / kWave] = sum;
-            sh_min[tid / kWave] = mn;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            for (int i = 1; i < kConfThreads / kWave; ++i) {
-                sum += sh_sum[i];
-                mn = sh_min[i] < mn ? sh_min[i] : mn;
-            }
-            w[b] = weight_mode == 0 ? (float)((double)mn / 1073741824.0)
-                                    : (float)((double)sum / ((double)len * 1073741824.0));
+        if (in && sub == 0) {
+            const bool ok = ans >= 0 && len > 0;
+            a[b] = ok ? ans : -1;
+            w[b] = !ok ? 0.f
+                       : (weight_mode == 0 ? (float)((double)mn / 1073741824.0)
+                                           : (float)((double)sum / ((double)len * 1073741824.0)));
         }
     }
     __syncthreads();

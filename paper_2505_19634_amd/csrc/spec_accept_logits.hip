@@ -12,9 +12,10 @@
 // U = trunc(u * 2^24); residual weights W_v = max(0, Ep_v * Sq - Eq_v * Sp); bonus weights Ep_v;
 // token = first v whose prefix sum exceeds floor(U_k * sum W / 2^24).  128-bit integers.
 //
-// Three launches:
-//   lg_rowstats_kernel  one 1024-thread workgroup per logit row (B * (2k + 1) rows): row maximum,
-//                       then S; the second sweep of the row is served by the L2.
+// Four launches:
+//   lg_max_kernel, lg_sum_kernel   grid (pieces of 16384 logits, B * (2k + 1) rows): piece maxima, then --
+//                       with the row maximum known -- the pieces' integer weight sums; the second sweep
+//                       of the logits is served by the L2 / memory-side cache.
 //   lg_scan_kernel      grid (chunks, B): accept tests -> n; 128-bit chunk sums of the weights of row n.
 //   lg_pick_kernel      grid (B): chunk and token where the integer CDF crosses the threshold.
 #include "lotts_common.h"
@@ -25,7 +26,7 @@ typedef unsigned __int128 u128;
 
 constexpr int kLgThreads = 256;
 constexpr int kLgWaves = kLgThreads / kWave;
-constexpr int kLgStatThreads = 1024;
+constexpr int kLgPiece = 16384;      // logits per piece of the row statistics (V <= 2^20: at most 64 pieces)
 constexpr int kLgChunk = 2048;       // tokens per chunk: 8 per thread
 constexpr int kLgMaxChunks = 512;    // V <= 2^20
 constexpr int kLgMaxK = kLgThreads;
@@ -51,15 +52,16 @@ __device__ __forceinline__ float pow2_neg_poly(float f) {
 }
 
 // E = trunc(2^t * 2^30) through the definition's steps; every operation individually rounded
-__device__ __forceinline__ unsigned long long logit_weight(float y, float m) {
+// (the weight is at most 2^30, so the conversion is a 32-bit one)
+__device__ __forceinline__ unsigned logit_weight(float y, float m) {
     const float t = __fmul_rn(__fsub_rn(y, m), 0x1.715476p+0f);
     const float a = -t;
     const float nf = floorf(a);
-    if (!(nf < 31.0f)) return 0ull;
+    if (!(nf < 31.0f)) return 0u;
     const float f = __fsub_rn(a, nf);
     const float g = pow2_neg_poly(f);
     const float scale = __uint_as_float((unsigned)(127 + 30 - (int)nf) << 23);  // 2^(30 - n), exact
-    return __float2ull_rz(__fmul_rn(g, scale));
+    return __float2uint_rz(__fmul_rn(g, scale));
 }
 
 template <bool BF16>
@@ -135,56 +137,87 @@ __device__ __forceinline__ u128 block_excl_scan_u128(u128 v, u128* sh /*[kLgWave
 __device__ __forceinline__ int trow(int b, int j, int k) { return b * (k + 1) + j; }
 __device__ __forceinline__ int drow(int B, int b, int j, int k) { return B * (k + 1) + b * k + j; }
 
+// Row statistics in two sweeps over pieces of kLgPiece logits (grid: pieces per row x rows), so that a
+// row is spread over many compute units: piece maxima first; then, with the row maximum known, the
+// integer weight sums of the pieces.  The second sweep finds the logits in the L2 / memory-side cache.
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kLgStatThreads) void lg_rowstats_kernel(int B, int k, int V, const void* __restrict__ zt,
-                                                                     const void* __restrict__ zd, float inv_temp,
-                                                                     RowStat* __restrict__ stats) {
-    __shared__ float sh_m[kLgStatThreads / kWave];
-    __shared__ unsigned long long sh_s[kLgStatThreads / kWave];
-    const int r = blockIdx.x, tid = threadIdx.x;
+__global__ __launch_bounds__(kLgThreads) void lg_max_kernel(int B, int k, int V, int npieces, const void* __restrict__ zt,
+                                                            const void* __restrict__ zd, float inv_temp,
+                                                            float* __restrict__ pmax) {
+    __shared__ float sh_m[kLgWaves];
+    const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
     const int nt = B * (k + 1);
     const void* z = r < nt ? zt : zd;
     const size_t base = (size_t)(r < nt ? r : r - nt) * V;
-    // sweep 1: maximum
+    const int lo = pc * kLgPiece, hi = min(V, lo + kLgPiece);
     float m = -INFINITY;
     if (VEC) {
-        for (int i = tid * 8; i < V; i += kLgStatThreads * 8) {
+        for (int i = lo + tid * 8; i < hi; i += kLgThreads * 8) {
             float y[8];
             load_y8<BF16>(z, base + i, inv_temp, y);
 #pragma unroll
             for (int e = 0; e < 8; ++e) m = fmaxf(m, y[e]);
         }
     } else {
-        for (int i = tid; i < V; i += kLgStatThreads) m = fmaxf(m, load_y<BF16>(z, base + i, inv_temp));
+        for (int i = lo + tid; i < hi; i += kLgThreads) m = fmaxf(m, load_y<BF16>(z, base + i, inv_temp));
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, kWave));
     if ((tid & (kWave - 1)) == 0) sh_m[tid / kWave] = m;
     __syncthreads();
-    m = sh_m[0];
+    if (tid == 0) {
 #pragma unroll
-    for (int w = 1; w < kLgStatThreads / kWave; ++w) m = fmaxf(m, sh_m[w]);
-    // sweep 2: sum of the integer weights
+        for (int w = 1; w < kLgWaves; ++w) m = fmaxf(m, sh_m[w]);
+        pmax[(size_t)r * npieces + pc] = m;
+    }
+}
+
+// maximum of a row from its piece maxima (npieces <= 64: one value per lane at most)
+__device__ __forceinline__ float row_max(const float* pmax, int row, int npieces) {
+    float m = -INFINITY;
+    for (int i = 0; i < npieces; ++i) m = fmaxf(m, pmax[(size_t)row * npieces + i]);
+    return m;
+}
+__device__ __forceinline__ RowStat row_stat(const float* pmax, const unsigned long long* psum_row, int row, int npieces) {
+    RowStat st;
+    st.m = row_max(pmax, row, npieces);
+    st.pad = 0.f;
+    st.S = 0;
+    for (int i = 0; i < npieces; ++i) st.S += psum_row[(size_t)row * npieces + i];
+    return st;
+}
+
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V, int npieces, const void* __restrict__ zt,
+                                                            const void* __restrict__ zd, float inv_temp,
+                                                            const float* __restrict__ pmax,
+                                                            unsigned long long* __restrict__ rsum) {
+    __shared__ unsigned long long sh_s[kLgWaves];
+    const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
+    const int nt = B * (k + 1);
+    const void* z = r < nt ? zt : zd;
+    const size_t base = (size_t)(r < nt ? r : r - nt) * V;
+    const int lo = pc * kLgPiece, hi = min(V, lo + kLgPiece);
+    const float m = row_max(pmax, r, npieces);
     unsigned long long s = 0;
     if (VEC) {
-        for (int i = tid * 8; i < V; i += kLgStatThreads * 8) {
+        for (int i = lo + tid * 8; i < hi; i += kLgThreads * 8) {
             float y[8];
             load_y8<BF16>(z, base + i, inv_temp, y);
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += logit_weight(y[e], m);
         }
     } else {
-        for (int i = tid; i < V; i += kLgStatThreads) s += logit_weight(load_y<BF16>(z, base + i, inv_temp), m);
+        for (int i = lo + tid; i < hi; i += kLgThreads) s += logit_weight(load_y<BF16>(z, base + i, inv_temp), m);
     }
     s = wave_sum_u64(s);
     if ((tid & (kWave - 1)) == 0) sh_s[tid / kWave] = s;
     __syncthreads();
     if (tid == 0) {
         unsigned long long tot = 0;
-        for (int w = 0; w < kLgStatThreads / kWave; ++w) tot += sh_s[w];
-        stats[r].m = m;
-        stats[r].pad = 0.f;
-        stats[r].S = tot;
+#pragma unroll
+        for (int w = 0; w < kLgWaves; ++w) tot += sh_s[w];
+        rsum[(size_t)r * npieces + pc] = tot;
     }
 }
 
@@ -192,13 +225,15 @@ __global__ __launch_bounds__(kLgStatThreads) void lg_rowstats_kernel(int B, int 
 template <bool BF16>
 __device__ __forceinline__ int lg_accepted_length(int B, int b, int k, int V, const void* zt, const void* zd,
                                                   float inv_temp, const int32_t* draft, const float* u,
-                                                  const RowStat* stats, int* sh_first) {
+                                                  const float* pmax, const unsigned long long* rsum, int npieces,
+                                                  int* sh_first) {
     const int tid = threadIdx.x;
     bool rejected = false;
     if (tid < k) {
         int x = draft[(size_t)b * k + tid];
         x = x < 0 ? 0 : (x >= V ? V - 1 : x);
-        const RowStat sp = stats[trow(b, tid, k)], sq = stats[drow(B, b, tid, k)];
+        const RowStat sp = row_stat(pmax, rsum, trow(b, tid, k), npieces);
+        const RowStat sq = row_stat(pmax, rsum, drow(B, b, tid, k), npieces);
         const unsigned long long Ep = logit_weight(load_y<BF16>(zt, (size_t)trow(b, tid, k) * V + x, inv_temp), sp.m);
         const unsigned long long Eq = logit_weight(load_y<BF16>(zd, ((size_t)b * k + tid) * V + x, inv_temp), sq.m);
         const u128 U = (u128)(unsigned)(u[(size_t)b * (k + 1) + tid] * 16777216.0f);
@@ -249,20 +284,21 @@ __global__ __launch_bounds__(kLgThreads) void lg_scan_kernel(int B, int k, int V
                                                              const void* __restrict__ zd, float inv_temp,
                                                              const int32_t* __restrict__ draft,
                                                              const float* __restrict__ u,
-                                                             const RowStat* __restrict__ stats,
+                                                             const float* __restrict__ pmax,
+                                                             const unsigned long long* __restrict__ rsum, int npieces,
                                                              int32_t* __restrict__ accept_len, u128* __restrict__ wsum,
                                                              unsigned long long* __restrict__ psum) {
     __shared__ int sh_first[kLgWaves];
     __shared__ u128 sh_w[kLgWaves];
     const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
-    const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, stats, sh_first);
+    const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, pmax, rsum, npieces, sh_first);
     if (c == 0 && tid == 0) accept_len[b] = n;
     const bool residual = n < k;
     const size_t es = BF16 ? 2 : 4;
     const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
     const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
-    const RowStat sp = stats[trow(b, n, k)];
-    const RowStat sq = residual ? stats[drow(B, b, n, k)] : sp;
+    const RowStat sp = row_stat(pmax, rsum, trow(b, n, k), npieces);
+    const RowStat sq = residual ? row_stat(pmax, rsum, drow(B, b, n, k), npieces) : sp;
     u128 W[8];
     unsigned long long Ep[8];
     lg_weights8<BF16, VEC>(zt_row, zd_row, c * kLgChunk + tid * 8, V, inv_temp, residual, sp, sq, W, Ep);
@@ -284,7 +320,8 @@ template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
                                                              const void* __restrict__ zd, float inv_temp,
                                                              const float* __restrict__ u,
-                                                             const RowStat* __restrict__ stats,
+                                                             const float* __restrict__ pmax,
+                                                             const unsigned long long* __restrict__ rsum, int npieces,
                                                              const int32_t* __restrict__ accept_len,
                                                              const u128* __restrict__ wsum,
                                                              const unsigned long long* __restrict__ psum,
@@ -329,8 +366,8 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
     const size_t es = BF16 ? 2 : 4;
     const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
     const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
-    const RowStat sp = stats[trow(b, n, k)];
-    const RowStat sq = residual ? stats[drow(B, b, n, k)] : sp;
+    const RowStat sp = row_stat(pmax, rsum, trow(b, n, k), npieces);
+    const RowStat sq = residual ? row_stat(pmax, rsum, drow(B, b, n, k), npieces) : sp;
     u128 W[8];
     unsigned long long Ep[8];
     const int lo = c * kLgChunk + tid * 8;
@@ -353,17 +390,20 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
 }
 
 struct LgLayout {
-    size_t off_stats, off_wsum, off_psum, total;
-    int nchunks;
+    size_t off_pmax, off_rsum, off_wsum, off_psum, total;
+    int nchunks, npieces;
 };
 static inline LgLayout lg_layout(int B, int k, int V) {
     LgLayout l;
     l.nchunks = (V + kLgChunk - 1) / kLgChunk;
+    l.npieces = (V + kLgPiece - 1) / kLgPiece;
     const size_t rows = (size_t)B * (2 * k + 1);
-    l.off_stats = 0;
-    l.off_wsum = (rows * sizeof(RowStat) + 255) & ~(size_t)255;
-    l.off_psum = l.off_wsum + (((size_t)B * l.nchunks * sizeof(u128) + 255) & ~(size_t)255);
-    l.total = l.off_psum + (((size_t)B * l.nchunks * sizeof(unsigned long long) + 255) & ~(size_t)255);
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    l.off_pmax = 0;
+    l.off_rsum = up(rows * l.npieces * sizeof(float));
+    l.off_wsum = l.off_rsum + up(rows * l.npieces * sizeof(unsigned long long));
+    l.off_psum = l.off_wsum + up((size_t)B * l.nchunks * sizeof(u128));
+    l.total = l.off_psum + up((size_t)B * l.nchunks * sizeof(unsigned long long));
     return l;
 }
 static inline bool lg_sizes_ok(int B, int k, int V) {
@@ -374,19 +414,24 @@ template <bool BF16, bool VEC>
 static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float inv_temp, const int32_t* draft,
                      const float* u, int32_t* accept_len, int32_t* next_token, void* workspace, hipStream_t s) {
     const LgLayout l = lg_layout(B, k, V);
-    RowStat* stats = reinterpret_cast<RowStat*>(static_cast<char*>(workspace) + l.off_stats);
+    float* pmax = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.off_pmax);
+    unsigned long long* rsum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_rsum);
     u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
     unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
-    hipLaunchKernelGGL((lg_rowstats_kernel<BF16, VEC>), dim3(B * (2 * k + 1)), dim3(kLgStatThreads), 0, s, B, k, V, zt, zd,
-                       inv_temp, stats);
+    const dim3 sgrid(l.npieces, B * (2 * k + 1));
+    hipLaunchKernelGGL((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), 0, s, B, k, V, l.npieces, zt, zd, inv_temp, pmax);
     int rc = check_launch();
     if (rc != LOTTS_OK) return rc;
+    hipLaunchKernelGGL((lg_sum_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), 0, s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
+                       rsum);
+    rc = check_launch();
+    if (rc != LOTTS_OK) return rc;
     hipLaunchKernelGGL((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd,
-                       inv_temp, draft, u, stats, accept_len, wsum, psum);
+                       inv_temp, draft, u, pmax, rsum, l.npieces, accept_len, wsum, psum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
     hipLaunchKernelGGL((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
-                       stats, accept_len, wsum, psum, next_token);
+                       pmax, rsum, l.npieces, accept_len, wsum, psum, next_token);
     return check_launch();
 }
 
