@@ -184,6 +184,21 @@ int confidence_vote(int32_t N, int32_t B, int32_t T, const int32_t *answers, con
                     const int32_t *conf_len, int32_t weight_mode, int32_t select_mode, int32_t *winner,
                     float *winner_score, void *stream);
 
+/*
+ * greedy_search -- the search for the latency-optimal configuration (B*, gamma*) of Algorithm 1
+ * (Section 3.3).  HOST function: it launches nothing; `tts_task(B, gamma, T, user)` is the
+ * caller's evaluation of the accuracy reached with B branches and draft length gamma under the
+ * latency budget T.  From (1, 0), each round evaluates (2B, gamma) and (B, gamma + 1), moves to
+ * the better one (the branch move on a tie) if it is strictly better than the current accuracy,
+ * and stops otherwise.  Moves beyond B_max / gamma_max are not evaluated.
+ *   B_opt, gamma_opt, acc_opt: out, required.  rounds (iterations of the loop, the terminating
+ *   one included: log2 B* + gamma* + 1 when no bound binds) and evaluations (calls of tts_task):
+ *   out, may be NULL.
+ */
+typedef double (*lotts_tts_task_fn)(int32_t B, int32_t gamma, double T, void *user);
+int greedy_search(lotts_tts_task_fn tts_task, void *user, double T, int32_t B_max, int32_t gamma_max,
+                  int32_t *B_opt, int32_t *gamma_opt, double *acc_opt, int32_t *rounds, int32_t *evaluations);
+
 #ifdef __cplusplus
 }
 #endif

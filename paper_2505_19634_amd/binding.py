@@ -18,7 +18,7 @@ LOTTS_F32, LOTTS_BF16 = 0, 1
 
 EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
            "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
-           "majority_vote", "confidence_vote")
+           "majority_vote", "confidence_vote", "greedy_search")
 
 
 class AttnDesc(ctypes.Structure):
@@ -31,6 +31,9 @@ class AttnDesc(ctypes.Structure):
                 ("kpriv_stride_b", ctypes.c_int64), ("kpriv_stride_h", ctypes.c_int64),
                 ("kpriv_stride_t", ctypes.c_int64),
                 ("o_stride_b", ctypes.c_int64), ("o_stride_r", ctypes.c_int64), ("o_stride_h", ctypes.c_int64)]
+
+
+TTS_TASK_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_void_p)
 
 
 class LottsError(RuntimeError):
@@ -66,6 +69,10 @@ def load() -> ctypes.CDLL:
         lib.spec_accept_logits_workspace_bytes.argtypes = [i32, i32, i32]
         lib.spec_accept_logits.restype = ctypes.c_int
         lib.spec_accept_logits.argtypes = [i32, i32, i32, vp, vp, i32, ctypes.c_float] + [vp] * 4 + [vp, sz, vp]
+        lib.greedy_search.restype = ctypes.c_int
+        lib.greedy_search.argtypes = [TTS_TASK_FN, vp, ctypes.c_double, i32, i32, ctypes.POINTER(ctypes.c_int32),
+                                      ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         lib.confidence_vote.restype = ctypes.c_int
         lib.confidence_vote.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp]
         _lib = lib
@@ -278,3 +285,19 @@ def confidence_vote(answers: torch.Tensor, conf: torch.Tensor, conf_len: Optiona
     if rc != 0:
         raise LottsError(rc, "confidence_vote")
     return winner, score
+
+
+def greedy_search(tts_task, T: float, B_max: int = 64, gamma_max: int = 7):
+    """Algorithm 1 on the host: tts_task(B, gamma, T) -> accuracy.  Returns (B, gamma, acc, rounds, evaluations)."""
+    lib = load()
+    cb = TTS_TASK_FN(lambda B, g, t, _user: float(tts_task(int(B), int(g), float(t))))
+    B = ctypes.c_int32()
+    g = ctypes.c_int32()
+    acc = ctypes.c_double()
+    rounds = ctypes.c_int32()
+    evals = ctypes.c_int32()
+    rc = lib.greedy_search(cb, None, float(T), int(B_max), int(gamma_max), ctypes.byref(B), ctypes.byref(g),
+                           ctypes.byref(acc), ctypes.byref(rounds), ctypes.byref(evals))
+    if rc != 0:
+        raise LottsError(rc, "greedy_search")
+    return B.value, g.value, acc.value, rounds.value, evals.value

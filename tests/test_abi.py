@@ -21,6 +21,7 @@ def lib():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "lotts.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"typedef[^;]*\(\s*\*[^;]*;", "", text)          # function-pointer typedefs declare no symbol
     return sorted(set(re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*\([^;{]*\)\s*;", text)))
 
 
