@@ -473,3 +473,26 @@ int oracle_confidence_vote(int N, int B, int T, const int32_t *answers, const fl
     }
     return 0;
 }
+
+/* =====================================================================================
+ * Widening 3: the weight GEMM of the verify forward.  The target model's forward over the
+ * B * (k + 1) new tokens multiplies a skinny activation matrix by every weight matrix, and the
+ * weights are what the step loads most of (Section 3.1; Appendix: 64 GB of weights for the 32B
+ * model against 0.25 GB of KV cache per branch).
+ *   Y[m][n] = sum_k X[m][k] * W[n][k]        X [M][K], W [N][K] (a Linear layer's weight), Y [M][N]
+ * bf16 (or fp32) inputs read exactly, fp64 accumulation, fp64 output.
+ * ===================================================================================== */
+int oracle_skinny_gemm(int M, int N, int K, int dtype, const void *X, const void *W, double *Y)
+{
+    if (M < 1 || N < 1 || K < 1 || !X || !W || !Y)
+        return -1;
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += load_elem(X, dtype, (int64_t)m * K + k) * load_elem(W, dtype, (int64_t)n * K + k);
+            Y[(int64_t)m * N + n] = acc;
+        }
+    return 0;
+}

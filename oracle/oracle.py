@@ -41,6 +41,8 @@ def _load():
         lib.oracle_logit_weights.argtypes = [c_int, vp, c_int, ctypes.c_float, vp]
         lib.oracle_spec_accept_logits.restype = c_int
         lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 4
+        lib.oracle_skinny_gemm.restype = c_int
+        lib.oracle_skinny_gemm.argtypes = [c_int] * 4 + [vp] * 3
         lib.oracle_confidence_vote.restype = c_int
         lib.oracle_confidence_vote.argtypes = [c_int] * 3 + [vp] * 3 + [c_int] * 2 + [vp] * 2
         _lib = lib
@@ -173,3 +175,17 @@ def confidence_vote(answers, conf, conf_len=None, weight_mode: str = "avg", sele
     if rc != 0:
         raise ValueError("oracle_confidence_vote rejected the call (rc=%d)" % rc)
     return w, s
+
+
+def skinny_gemm(X, W):
+    """Y = X @ W.T in fp64.  X [M][K], W [N][K], float32 or uint16 (bf16 bit patterns)."""
+    X, dt = _kv(X)
+    W, dt2 = _kv(W)
+    assert dt == dt2 and X.shape[1] == W.shape[1]
+    M, K = X.shape
+    N = W.shape[0]
+    Y = np.empty((M, N), dtype=np.float64)
+    rc = _load().oracle_skinny_gemm(M, N, K, dt, _ptr(X), _ptr(W), _ptr(Y))
+    if rc != 0:
+        raise ValueError("oracle_skinny_gemm rejected the call (rc=%d)" % rc)
+    return Y
