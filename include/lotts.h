@@ -184,6 +184,25 @@ int confidence_vote(int32_t N, int32_t B, int32_t T, const int32_t *answers, con
                     const int32_t *conf_len, int32_t weight_mode, int32_t select_mode, int32_t *winner,
                     float *winner_score, void *stream);
 
+/* Bytes of workspace skinny_gemm needs (0 if the sizes are invalid). */
+size_t skinny_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
+ * skinny_gemm -- one weight GEMM of the verify forward: the B * (k + 1) new tokens against a
+ * Linear layer's weight (Section 3.1: the step is bound by loading the weights; Appendix: 64 GB of
+ * weights for the 32B model).
+ *   Y[m][n] = sum_k X[m][k] * W[n][k]
+ *   X [M][K] bf16 (row pitch ldx elements), W [N][K] bf16 (ldw), Y [M][N] bf16 out (ldy)
+ *   1 <= M <= 128; N a multiple of 8; K a multiple of 128; ldx, ldw multiples of 8, ldy of 4;
+ *   X, W, workspace 16-byte aligned, Y 8-byte aligned
+ * bf16 products accumulate in fp32 on the matrix cores; W is read from HBM once.  When N is
+ * small the K range is split over workgroups and the fp32 partials are summed in a fixed order
+ * by a second launch (deterministic).
+ *   workspace: >= skinny_gemm_workspace_bytes(M, N, K), any contents
+ */
+int skinny_gemm(int32_t M, int32_t N, int32_t K, const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y,
+                int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
 /*
  * greedy_search -- the search for the latency-optimal configuration (B*, gamma*) of Algorithm 1
  * (Section 3.3).  HOST function: it launches nothing; `tts_task(B, gamma, T, user)` is the

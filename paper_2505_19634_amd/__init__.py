@@ -4,7 +4,8 @@ The product is liblotts.so (csrc/, C ABI in include/lotts.h); this package is it
 binding.  Importing it loads the library and fails loudly if it has not been built.
 """
 from .binding import (AttnDesc, LottsError, load, strerror, verify_attention, spec_accept,  # noqa: F401
-                      spec_accept_logits, majority_vote, confidence_vote, greedy_search, make_attn_desc,
+                      spec_accept_logits, majority_vote, confidence_vote, greedy_search, skinny_gemm,
+                      make_attn_desc,
                       EXPORTS, LIB_PATH)
 
 load()

@@ -18,7 +18,7 @@ LOTTS_F32, LOTTS_BF16 = 0, 1
 
 EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
            "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
-           "majority_vote", "confidence_vote", "greedy_search")
+           "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "greedy_search")
 
 
 class AttnDesc(ctypes.Structure):
@@ -69,6 +69,10 @@ def load() -> ctypes.CDLL:
         lib.spec_accept_logits_workspace_bytes.argtypes = [i32, i32, i32]
         lib.spec_accept_logits.restype = ctypes.c_int
         lib.spec_accept_logits.argtypes = [i32, i32, i32, vp, vp, i32, ctypes.c_float] + [vp] * 4 + [vp, sz, vp]
+        lib.skinny_gemm_workspace_bytes.restype = sz
+        lib.skinny_gemm_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.skinny_gemm.restype = ctypes.c_int
+        lib.skinny_gemm.argtypes = [i32, i32, i32, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, sz, vp]
         lib.greedy_search.restype = ctypes.c_int
         lib.greedy_search.argtypes = [TTS_TASK_FN, vp, ctypes.c_double, i32, i32, ctypes.POINTER(ctypes.c_int32),
                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
@@ -301,3 +305,26 @@ def greedy_search(tts_task, T: float, B_max: int = 64, gamma_max: int = 7):
     if rc != 0:
         raise LottsError(rc, "greedy_search")
     return B.value, g.value, acc.value, rounds.value, evals.value
+
+
+def skinny_gemm(X: torch.Tensor, W: torch.Tensor, *, out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Y = X @ W.T for bf16 X [M][K] (M <= 128) and W [N][K] on the GPU; rows may be strided."""
+    lib = load()
+    if not X.is_cuda or X.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
+        raise TypeError("skinny_gemm takes bfloat16 tensors on the GPU")
+    M, K = X.shape
+    N, K2 = W.shape
+    if K2 != K or X.stride(1) != 1 or W.stride(1) != 1:
+        raise ValueError("X [M][K] and W [N][K] must share K and have contiguous rows")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    need = lib.skinny_gemm_workspace_bytes(M, N, K)
+    if need == 0:
+        raise LottsError(-2, "skinny_gemm_workspace_bytes")
+    ws = _workspace("gemm", X.device, need) if workspace is None else workspace
+    rc = lib.skinny_gemm(M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(out), out.stride(0), _ptr(ws),
+                         ws.numel() * ws.element_size(), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "skinny_gemm")
+    return out

@@ -1,0 +1,213 @@
+// skinny_gemm: Y[M][N] = X[M][K] W[N][K]^T for the B * (k + 1) new tokens of a verify forward (M of a few
+// tens) against one weight matrix (paper Section 3.1: the step is bound by loading the weights; Appendix:
+// 64 GB of weights for the 32B model).  bf16 in, fp32 accumulate on the matrix cores, bf16 out.
+// HBM-bound on streaming W once: 2 * M flop per weight byte is far below the MFMA balance.
+//
+//   skinny_gemm_kernel<MT>  grid (blocks of 128 weight rows, K splits).  Each of the 4 wavefronts owns 32
+//       weight rows and walks the K range in chunks of 128: the W tile (32 x 128, 8 KB) comes in with
+//       coalesced non-temporal 16-byte loads one chunk ahead, is staged through a wavefront-private LDS
+//       slab and read back as the MFMA A operand; the X chunk (up to 128 x 128) is fetched once per
+//       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
+//       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
+//   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
+//       partials in a fixed order and converts.
+#include "lotts_common.h"
+
+namespace lotts {
+
+typedef __bf16 g_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 g_bf16x4 __attribute__((ext_vector_type(4)));
+typedef float g_f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned g_u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kGemmThreads = 256;
+constexpr int kGemmWaves = 4;
+constexpr int kGemmRows = 32;                         // weight rows per wavefront = M of the MFMA
+constexpr int kGemmBlockN = kGemmWaves * kGemmRows;   // weight rows per workgroup
+constexpr int kGemmChunk = 128;                       // K elements per chunk
+constexpr int kGemmRowBytes = kGemmChunk * 2 + 16;    // LDS row pitch: conflict-free 16-byte row reads
+constexpr int kGemmMaxM = 128;
+
+struct GemmParams {
+    const __bf16 *X, *W;
+    __bf16* Y;
+    float* part;  // [ksplit][M][N] fp32 when ksplit > 1
+    int M, N, K, ksplit;
+    long long ldx, ldw, ldy;
+};
+
+struct GemmPlan {
+    int mt, nblocks, ksplit;
+};
+static inline GemmPlan plan_gemm(int M, int N, int K) {
+    GemmPlan pl;
+    pl.mt = (M + 31) / 32;
+    pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
+    const int chunks = K / kGemmChunk;
+    int ks = (kNumCU + pl.nblocks - 1) / pl.nblocks;  // about one workgroup per compute unit
+    const int max_ks = chunks / 4 > 0 ? chunks / 4 : 1;
+    if (ks > max_ks) ks = max_ks;
+    if (ks > 16) ks = 16;
+    pl.ksplit = ks < 1 ? 1 : ks;
+    return pl;
+}
+
+template <int MT>
+__global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_kernel(const GemmParams p) {
+    constexpr int XROWS = 32 * MT;
+    __shared__ __attribute__((aligned(16))) unsigned char xbuf[2][XROWS * kGemmRowBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][kGemmRows * kGemmRowBytes];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int ln = lane & 31, hh = lane >> 5;
+    const int n0 = blockIdx.x * kGemmBlockN + wave * kGemmRows;
+    const int chunks = p.K / kGemmChunk;
+    const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
+    const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
+    unsigned char* wslab = wslab_all[wave];
+
+    // W tile: 8 load instructions, each covering 4 whole 256-byte row pieces
+    const int w_row = lane >> 4, w_ch = lane & 15;
+    g_u32x4 wst[8];
+    auto fetch_w = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int n = n0 + i * 4 + w_row;
+            n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
+            wst[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
+        }
+    };
+    // X chunk: XROWS rows x 16 pieces of 16 bytes, 2 * MT pieces per thread
+    g_u32x4 xst[2 * MT];
+    auto fetch_x = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < 2 * MT; ++i) {
+            const int idx = tid + i * kGemmThreads;
+            int m = idx >> 4;
+            m = m < p.M ? m : p.M - 1;
+            xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
+        }
+    };
+    g_f32x16 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    if (c_lo < c_hi) {
+        fetch_w(c_lo);
+        fetch_x(c_lo);
+    }
+    for (int c = c_lo; c < c_hi; ++c) {
+        unsigned char* xb = xbuf[(c - c_lo) & 1];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
+#pragma unroll
+        for (int i = 0; i < 2 * MT; ++i) {
+            const int idx = tid + i * kGemmThreads;
+            *reinterpret_cast<g_u32x4*>(xb + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
+        }
+        __syncthreads();  // the X chunk is complete; the other buffer is free for chunk c + 1
+        if (c + 1 < c_hi) {
+            fetch_w(c + 1);
+            fetch_x(c + 1);
+        }
+        // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const g_bf16x8 a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const g_bf16x8 b =
+                    *reinterpret_cast<const g_bf16x8*>(xb + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+            }
+        }
+    }
+    // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = t * 32 + ln;
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int n = n0 + q4 * 8 + hh * 4;
+            if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
+            if (p.ksplit == 1) {
+                g_bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[t][q4 * 4 + e];
+                *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
+            } else {
+                *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) =
+                    make_float4(acc[t][q4 * 4 + 0], acc[t][q4 * 4 + 1], acc[t][q4 * 4 + 2], acc[t][q4 * 4 + 3]);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void skinny_gemm_reduce_kernel(const GemmParams p) {
+    const long long i4 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;  // 4 consecutive columns of one row
+    if (i4 >= (long long)p.M * p.N) return;
+    const int m = (int)(i4 / p.N), n = (int)(i4 - (long long)m * p.N);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int ks = 0; ks < p.ksplit; ++ks) {  // fixed order: deterministic
+        const float4 v = *reinterpret_cast<const float4*>(p.part + ((long long)ks * p.M + m) * p.N + n);
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
+    }
+    g_bf16x4 o;
+    o[0] = (__bf16)s.x;
+    o[1] = (__bf16)s.y;
+    o[2] = (__bf16)s.z;
+    o[3] = (__bf16)s.w;
+    *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
+}
+
+static inline bool gemm_sizes_ok(int M, int N, int K) {
+    return M >= 1 && M <= kGemmMaxM && N >= 8 && (N % 8) == 0 && K >= kGemmChunk && (K % kGemmChunk) == 0 &&
+           (long long)M * N < (1LL << 40);
+}
+
+}  // namespace lotts
+
+extern "C" size_t skinny_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) {
+    if (!lotts::gemm_sizes_ok(M, N, K)) return 0;
+    const lotts::GemmPlan pl = lotts::plan_gemm(M, N, K);
+    const size_t bytes = pl.ksplit > 1 ? (size_t)pl.ksplit * M * N * sizeof(float) : 0;
+    return bytes < 256 ? 256 : bytes;
+}
+
+extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                           void* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lotts;
+    if (!gemm_sizes_ok(M, N, K)) return LOTTS_ERR_SHAPE;
+    if (!X || !W || !Y || !workspace) return LOTTS_ERR_NULL;
+    if (ldx < K || ldw < K || ldy < N || (ldx % 8) || (ldw % 8) || (ldy % 4)) return LOTTS_ERR_SHAPE;
+    if ((((uintptr_t)X | (uintptr_t)W | (uintptr_t)workspace) & 15) || ((uintptr_t)Y & 7)) return LOTTS_ERR_SHAPE;
+    if (workspace_bytes < skinny_gemm_workspace_bytes(M, N, K)) return LOTTS_ERR_WORKSPACE;
+    const GemmPlan pl = plan_gemm(M, N, K);
+    GemmParams p;
+    p.X = static_cast<const __bf16*>(X);
+    p.W = static_cast<const __bf16*>(W);
+    p.Y = static_cast<__bf16*>(Y);
+    p.part = static_cast<float*>(workspace);
+    p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit;
+    p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads);
+    switch (pl.mt) {
+        case 1: hipLaunchKernelGGL(skinny_gemm_kernel<1>, grid, block, 0, s, p); break;
+        case 2: hipLaunchKernelGGL(skinny_gemm_kernel<2>, grid, block, 0, s, p); break;
+        case 3: hipLaunchKernelGGL(skinny_gemm_kernel<3>, grid, block, 0, s, p); break;
+        default: hipLaunchKernelGGL(skinny_gemm_kernel<4>, grid, block, 0, s, p); break;
+    }
+    int rc = check_launch();
+    if (rc != LOTTS_OK || pl.ksplit == 1) return rc;
+    const long long quads = ((long long)M * N + 3) / 4;
+    hipLaunchKernelGGL(skinny_gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, p);
+    return check_launch();
+}

@@ -322,3 +322,39 @@ def test_confidence_vote(lotts, oracle, N, B, T):
                 w_ref, s_ref = oracle.confidence_vote(answers, conf, cl, wm, sm)
                 assert np.array_equal(w.cpu().numpy(), w_ref), (wm, sm)
                 assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), (wm, sm)
+
+
+# ---------------------------------------------------------------------------- weight GEMM of the verify forward
+@pytest.mark.parametrize("M,N,K", [
+    (64, 512, 1024), (40, 136, 256), (5, 8, 128), (1, 1000, 384), (128, 256, 512), (97, 264, 640),
+    (64, 7168, 5120),       # 32B-shaped QKV projection for B * (k + 1) = 64 tokens (K split over workgroups)
+    (64, 5120, 27648),      # 32B-shaped MLP down projection
+    (36, 27648, 5120),      # 32B-shaped MLP up projection, M of the long-draft config
+])
+def test_skinny_gemm(lotts, oracle, M, N, K):
+    print("gemm case", M, N, K, flush=True)
+    g = S.rng_for(7, 30, salt=M + N + K)
+    X = S.f32_to_bf16_bits(g.standard_normal((M, K), dtype=np.float32))
+    W = S.f32_to_bf16_bits(g.standard_normal((N, K), dtype=np.float32) * np.float32(K ** -0.5))
+    Y = lotts.skinny_gemm(to_dev(X, True), to_dev(W, True))
+    torch.cuda.synchronize()
+    ref = oracle.skinny_gemm(X, W)
+    y = Y.float().cpu().numpy().astype(np.float64)
+    # bf16 output rounding (2^-9 relative) dominates; fp32 accumulation over K adds ~1e-6
+    err = np.abs(y - ref)
+    assert (err <= 2.0 ** -8 * np.abs(ref) + 1e-3).all(), err.max()
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) <= 3e-3
+
+
+def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle):
+    g = S.rng_for(7, 31)
+    M, N, K = 48, 640, 768
+    Xf = torch.from_numpy(S.f32_to_bf16_bits(g.standard_normal((M, K + 64), dtype=np.float32))).to(DEV).view(torch.bfloat16)
+    Wf = torch.from_numpy(S.f32_to_bf16_bits(g.standard_normal((N, K + 8), dtype=np.float32) * 0.03)).to(DEV).view(torch.bfloat16)
+    X, W = Xf[:, :K], Wf[:, :K]
+    out = torch.zeros((M, N + 12), dtype=torch.bfloat16, device=DEV)
+    Y1 = lotts.skinny_gemm(X, W, out=out[:, :N]).clone()
+    Y2 = lotts.skinny_gemm(X.contiguous(), W.contiguous())
+    assert torch.equal(Y1, Y2) and float(out[:, N:].abs().sum()) == 0.0
+    ref = oracle.skinny_gemm(X.contiguous().view(torch.uint16).cpu().numpy(), W.contiguous().view(torch.uint16).cpu().numpy())
+    assert np.linalg.norm(Y1.float().cpu().numpy() - ref) / np.linalg.norm(ref) <= 3e-3
