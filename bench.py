@@ -270,6 +270,35 @@ def main() -> int:
     out["confidence_vote"] = {"ms": sum(e[0].elapsed_time(e[1]) for e in evc) / len(evc), "scores_per_branch": Tc,
                               "mode": "avg-vote"}
 
+    # weight GEMMs of one 32B-shaped decoder layer for the step's M = B * (k + 1) tokens (hidden 5120,
+    # 40/8 heads of 128, MLP 27648): QKV, O, gate+up, down.  Weight copies are rotated like the KV sets.
+    Mg = min(cfg.B * cfg.R, 128)
+    gemms = {}
+    for name_, (Ng, Kg) in {"qkv_proj": (7168, 5120), "o_proj": (5120, 5120), "gate_up_proj": (55296, 5120),
+                            "down_proj": (5120, 27648)}.items():
+        ncopies = 3
+        Ws = [(torch.randn((Ng, Kg), generator=gen, device=dev) * Kg ** -0.5).to(torch.bfloat16) for _ in range(ncopies)]
+        Xg = torch.randn((Mg, Kg), generator=gen, device=dev).to(torch.bfloat16)
+        Yg = torch.empty((Mg, Ng), dtype=torch.bfloat16, device=dev)
+        wsb = lib.skinny_gemm_workspace_bytes(Mg, Ng, Kg)
+        wsg = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        call = lambda i: lib.skinny_gemm(Mg, Ng, Kg, P(Xg), Kg, P(Ws[i % ncopies]), Kg, P(Yg), Ng, P(wsg), wsb, sh)
+        for i in range(6):
+            assert call(i) == 0
+        evg = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(40)]
+        for i, e in enumerate(evg):
+            e[0].record(stream)
+            call(i)
+            e[1].record(stream)
+        torch.cuda.synchronize()
+        ms = sum(e[0].elapsed_time(e[1]) for e in evg) / len(evg)
+        nbytes = 2 * (Ng * Kg + Mg * Kg + Mg * Ng)
+        gemms[name_] = {"M": Mg, "N": Ng, "K": Kg, "ms": ms, "algorithmic_bytes": nbytes,
+                        "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "TFLOP/s": 2.0 * Mg * Ng * Kg / (ms * 1e-3) / 1e12}
+        del Ws, Xg, Yg, wsg
+    out["skinny_gemm"] = gemms
+
     # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
     if not args.no_cpu_baseline:
         import oracle
