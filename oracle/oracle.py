@@ -25,27 +25,32 @@ def build(force: bool = True) -> str:
     return _LIB
 
 
+def _bind(lib):
+    """Declare the C signatures on a loaded oracle library (also used by the tests that load
+    deliberately broken copies of it)."""
+    c_int, c_dbl, vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+    lib.oracle_verify_attention.restype = c_int
+    lib.oracle_verify_attention.argtypes = [c_int] * 8 + [c_dbl] + [vp] * 8
+    lib.oracle_spec_accept.restype = c_int
+    lib.oracle_spec_accept.argtypes = [c_int] * 3 + [vp] * 6
+    lib.oracle_majority_vote.restype = c_int
+    lib.oracle_majority_vote.argtypes = [c_int] * 2 + [vp] * 3
+    lib.oracle_logit_weights.restype = ctypes.c_uint64
+    lib.oracle_logit_weights.argtypes = [c_int, vp, c_int, ctypes.c_float, vp]
+    lib.oracle_spec_accept_logits.restype = c_int
+    lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 4
+    lib.oracle_skinny_gemm.restype = c_int
+    lib.oracle_skinny_gemm.argtypes = [c_int] * 4 + [vp] * 3
+    lib.oracle_confidence_vote.restype = c_int
+    lib.oracle_confidence_vote.argtypes = [c_int] * 3 + [vp] * 3 + [c_int] * 2 + [vp] * 2
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
         build(force=False)
-        lib = ctypes.CDLL(_LIB)
-        c_int, c_dbl, vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
-        lib.oracle_verify_attention.restype = c_int
-        lib.oracle_verify_attention.argtypes = [c_int] * 8 + [c_dbl] + [vp] * 8
-        lib.oracle_spec_accept.restype = c_int
-        lib.oracle_spec_accept.argtypes = [c_int] * 3 + [vp] * 6
-        lib.oracle_majority_vote.restype = c_int
-        lib.oracle_majority_vote.argtypes = [c_int] * 2 + [vp] * 3
-        lib.oracle_logit_weights.restype = ctypes.c_uint64
-        lib.oracle_logit_weights.argtypes = [c_int, vp, c_int, ctypes.c_float, vp]
-        lib.oracle_spec_accept_logits.restype = c_int
-        lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 4
-        lib.oracle_skinny_gemm.restype = c_int
-        lib.oracle_skinny_gemm.argtypes = [c_int] * 4 + [vp] * 3
-        lib.oracle_confidence_vote.restype = c_int
-        lib.oracle_confidence_vote.argtypes = [c_int] * 3 + [vp] * 3 + [c_int] * 2 + [vp] * 2
-        _lib = lib
+        _lib = _bind(ctypes.CDLL(_LIB))
     return _lib
 
 
