@@ -341,18 +341,19 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         slot = split;
     }
     const int L_raw = is_private ? prm.priv_len[b_item] : 0;  // requested here, first used further down
+    // The 32-key tiles of a segment are dealt round-robin to all wavefronts working on it (the 4
+    // wavefronts of each of its nsplit items): every wavefront streams the same number of tiles to
+    // within one whatever the segment's length, and at any moment the wavefronts of a segment read
+    // neighbouring tiles, which spreads each item's traffic over the memory channels.
+    const int wave_of_seg = split * kAttnWaves + wave, waves_of_seg = nsplit * kAttnWaves;
     if (is_private && pl.fold) {
-        // this item's share of the prefix keys (groups of 4), dealt to the wavefronts tile by tile
-        const int pg = (prm.P + 3) >> 2;
-        const int p_lo = (int)((long long)split * pg / nsplit) * 4;
-        const int p_hi = min(prm.P, (int)((long long)(split + 1) * pg / nsplit) * 4);
         run[0].K = (const __bf16*)prm.Kpre + (long long)kvh * prm.kpre_stride_h;
         run[0].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
         run[0].stride_t = prm.kpre_stride_t;
-        run[0].lo = p_lo + wave * kTile;
-        run[0].hi = p_hi;
-        run[0].step = kAttnWaves * kTile;
-        run[0].ntiles = run[0].lo < p_hi ? (p_hi - run[0].lo + run[0].step - 1) / run[0].step : 0;
+        run[0].lo = wave_of_seg * kTile;
+        run[0].hi = prm.P;
+        run[0].step = waves_of_seg * kTile;
+        run[0].ntiles = run[0].lo < run[0].hi ? (run[0].hi - run[0].lo + run[0].step - 1) / run[0].step : 0;
     }
     const int n_fold = run[0].ntiles;
 
@@ -426,18 +427,10 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         run[1].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
         run[1].stride_t = prm.kpre_stride_t;
     }
-    // Keys of the item's own segment are dealt out in groups of 4 (one load instruction covers whole
-    // groups): the item takes an equal share of the groups and each of its wavefronts an equal,
-    // contiguous share of those, so all wavefronts stream the same number of bytes to within 4 keys.
-    {
-        const int ngroups = (seg_len + 3) >> 2;
-        const int g_lo = (int)((long long)split * ngroups / nsplit);
-        const int g_hi = (int)((long long)(split + 1) * ngroups / nsplit);
-        run[1].lo = (g_lo + (int)((long long)wave * (g_hi - g_lo) / kAttnWaves)) * 4;
-        run[1].hi = min(seg_len, (g_lo + (int)((long long)(wave + 1) * (g_hi - g_lo) / kAttnWaves)) * 4);
-        run[1].step = kTile;
-        run[1].ntiles = run[1].lo < run[1].hi ? (run[1].hi - run[1].lo + kTile - 1) / kTile : 0;
-    }
+    run[1].lo = wave_of_seg * kTile;
+    run[1].hi = seg_len;
+    run[1].step = waves_of_seg * kTile;
+    run[1].ntiles = run[1].lo < seg_len ? (seg_len - run[1].lo + run[1].step - 1) / run[1].step : 0;
     const int n_tiles = n_fold + run[1].ntiles;
     if (n_fold == 0 && n_tiles > 0) fetch(0);
     int lim[NQT];  // keys of this wavefront's own run visible to this lane's query row
@@ -461,7 +454,7 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     for (int it = 0; it < n_tiles; ++it) {
         if (it == 1) DBG_STAMP(2);
         const bool folded = it < n_fold;
-        const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * kTile;
+        const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * run[1].step;
 #pragma unroll
         for (int i = 0; i < NVL; ++i) {
             *reinterpret_cast<u32x4*>(kslab + (i * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
