@@ -243,7 +243,7 @@ def main() -> int:
         zt, zd = zsets[i % nsets]
         return lib.spec_accept_logits(cfg.B, cfg.k, cfg.V, P(zt), P(zd) if cfg.k else None, binding.LOTTS_BF16,
                                       ctypes.c_float(1.0), P(d0["draft"]) if cfg.k else None, P(d0["u"]),
-                                      P(d0["accept_len"]), P(d0["next_token"]), P(ws_lg), ws_lg_bytes, sh)
+                                      P(d0["accept_len"]), P(d0["next_token"]), None, P(ws_lg), ws_lg_bytes, sh)
     for i in range(8):
         assert lg_call(i) == 0
     evl = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(100)]

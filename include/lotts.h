@@ -146,12 +146,16 @@ size_t spec_accept_logits_workspace_bytes(int32_t B, int32_t k, int32_t V);
  *       LOTTS_BF16, finite or -inf; inv_temperature > 0
  *   draft [B][k] int32 (NULL iff k == 0), u [B][k+1] fp32 in [0, 1)
  *   accept_len [B], next_token [B] int32 out
+ *   priv_len [B] int32 in/out, NULL to skip: the private length verify_attention was given for
+ *       this step (it counts the k + 1 new tokens).  The k - accept_len[b] rejected drafts are
+ *       dropped from it, priv_len[b] -= k - accept_len[b], so it then counts exactly the tokens
+ *       whose keys and values stay valid; the caller appends the next step's k + 1 tokens there.
  *   workspace: >= spec_accept_logits_workspace_bytes(B, k, V), 16-byte aligned, any contents
  */
 int spec_accept_logits(int32_t B, int32_t k, int32_t V, const void *target_logits, const void *draft_logits,
                        int32_t logit_dtype, float inv_temperature, const int32_t *draft, const float *u,
-                       int32_t *accept_len, int32_t *next_token, void *workspace, size_t workspace_bytes,
-                       void *stream);
+                       int32_t *accept_len, int32_t *next_token, int32_t *priv_len, void *workspace,
+                       size_t workspace_bytes, void *stream);
 
 /*
  * majority_vote -- the answer most branches agree on (Section 1 and Section 4.1: branches are

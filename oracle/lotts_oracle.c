@@ -331,7 +331,8 @@ uint64_t oracle_logit_weights(int V, const void *z, int dtype, float inv_temp, u
 typedef unsigned __int128 u128;
 
 int oracle_spec_accept_logits(int B, int k, int V, const void *zt, const void *zd, int dtype, float inv_temp,
-                              const int32_t *draft, const float *u, int32_t *accept_len, int32_t *next_token)
+                              const int32_t *draft, const float *u, int32_t *accept_len, int32_t *next_token,
+                              int32_t *priv_len)
 {
     if (B < 1 || k < 0 || V < 1 || V > (1 << 20) || !zt || !u || !accept_len || !next_token ||
         (k > 0 && (!zd || !draft)) || !(inv_temp > 0.0f))
@@ -391,6 +392,8 @@ int oracle_spec_accept_logits(int B, int k, int V, const void *zt, const void *z
             }
         }
         next_token[b] = tok;
+        if (priv_len) /* the k - n rejected drafts leave the branch's KV cache */
+            priv_len[b] -= k - n;
         free(Ep);
         free(Eq);
     }

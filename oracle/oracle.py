@@ -38,7 +38,7 @@ def _bind(lib):
     lib.oracle_logit_weights.restype = ctypes.c_uint64
     lib.oracle_logit_weights.argtypes = [c_int, vp, c_int, ctypes.c_float, vp]
     lib.oracle_spec_accept_logits.restype = c_int
-    lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 4
+    lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 5
     lib.oracle_skinny_gemm.restype = c_int
     lib.oracle_skinny_gemm.argtypes = [c_int] * 4 + [vp] * 3
     lib.oracle_confidence_vote.restype = c_int
@@ -144,9 +144,10 @@ def logit_weights(z_row, inv_temp: float = 1.0):
     return E, int(S)
 
 
-def spec_accept_logits(zt, zd, draft, u, inv_temp: float = 1.0):
+def spec_accept_logits(zt, zd, draft, u, inv_temp: float = 1.0, priv_len=None):
     """Acceptance from target logits zt [B][k+1][V] and draft logits zd [B][k][V] (float32 or uint16 = bf16
-    bit patterns).  Returns (accept_len [B], next_token [B])."""
+    bit patterns).  Returns (accept_len [B], next_token [B]); priv_len (contiguous int32 [B], optional) is
+    updated in place: the rejected drafts are dropped from each branch's private length."""
     zt, dt = _kv(zt)
     B, R, V = zt.shape
     k = R - 1
@@ -159,8 +160,10 @@ def spec_accept_logits(zt, zd, draft, u, inv_temp: float = 1.0):
         zd, draft = None, None
     n = np.empty((B,), dtype=np.int32)
     t = np.empty((B,), dtype=np.int32)
+    if priv_len is not None:
+        assert priv_len.dtype == np.int32 and priv_len.shape == (B,) and priv_len.flags.c_contiguous
     rc = _load().oracle_spec_accept_logits(B, k, V, _ptr(zt), _ptr(zd), dt, float(inv_temp), _ptr(draft), _ptr(u),
-                                           _ptr(n), _ptr(t))
+                                           _ptr(n), _ptr(t), _ptr(priv_len))
     if rc != 0:
         raise ValueError("oracle_spec_accept_logits rejected the call (rc=%d)" % rc)
     return n, t

@@ -68,7 +68,7 @@ def load() -> ctypes.CDLL:
         lib.spec_accept_logits_workspace_bytes.restype = sz
         lib.spec_accept_logits_workspace_bytes.argtypes = [i32, i32, i32]
         lib.spec_accept_logits.restype = ctypes.c_int
-        lib.spec_accept_logits.argtypes = [i32, i32, i32, vp, vp, i32, ctypes.c_float] + [vp] * 4 + [vp, sz, vp]
+        lib.spec_accept_logits.argtypes = [i32, i32, i32, vp, vp, i32, ctypes.c_float] + [vp] * 5 + [vp, sz, vp]
         lib.skinny_gemm_workspace_bytes.restype = sz
         lib.skinny_gemm_workspace_bytes.argtypes = [i32, i32, i32]
         lib.skinny_gemm.restype = ctypes.c_int
@@ -228,10 +228,11 @@ def majority_vote(answers: torch.Tensor, *, winner: Optional[torch.Tensor] = Non
 
 def spec_accept_logits(target_logits: torch.Tensor, draft_logits: Optional[torch.Tensor], draft: Optional[torch.Tensor],
                        u: torch.Tensor, *, inv_temperature: float = 1.0, accept_len: Optional[torch.Tensor] = None,
-                       next_token: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                       stream: Optional[torch.cuda.Stream] = None):
+                       next_token: Optional[torch.Tensor] = None, priv_len: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
     """target_logits [B][k+1][V], draft_logits [B][k][V] (both bfloat16 or both float32, contiguous), draft [B][k]
-    int32, u [B][k+1] fp32, on the GPU.  Returns (accept_len [B] int32, next_token [B] int32)."""
+    int32, u [B][k+1] fp32, on the GPU.  Returns (accept_len [B] int32, next_token [B] int32).  priv_len (int32 [B],
+    optional) is updated in place: priv_len[b] -= k - accept_len[b]."""
     lib = load()
     if not target_logits.is_cuda:
         raise ValueError("spec_accept_logits runs on the GPU only")
@@ -256,13 +257,16 @@ def spec_accept_logits(target_logits: torch.Tensor, draft_logits: Optional[torch
         accept_len = torch.empty((B,), dtype=torch.int32, device=u.device)
     if next_token is None:
         next_token = torch.empty((B,), dtype=torch.int32, device=u.device)
+    if priv_len is not None and (priv_len.dtype != torch.int32 or tuple(priv_len.shape) != (B,) or
+                                 not priv_len.is_contiguous() or priv_len.device != u.device):
+        raise TypeError("priv_len must be a contiguous int32 [B] tensor on the same GPU")
     need = lib.spec_accept_logits_workspace_bytes(B, k, V)
     if need == 0:
         raise LottsError(-2, "spec_accept_logits_workspace_bytes")
     ws = _workspace("accept_logits", u.device, need) if workspace is None else workspace
     rc = lib.spec_accept_logits(B, k, V, _ptr(target_logits), _ptr(draft_logits), dt, float(inv_temperature), _ptr(draft),
-                                _ptr(u), _ptr(accept_len), _ptr(next_token), _ptr(ws), ws.numel() * ws.element_size(),
-                                _stream_handle(stream))
+                                _ptr(u), _ptr(accept_len), _ptr(next_token), _ptr(priv_len), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream_handle(stream))
     if rc != 0:
         raise LottsError(rc, "spec_accept_logits")
     return accept_len, next_token

@@ -325,12 +325,14 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
                                                              const int32_t* __restrict__ accept_len,
                                                              const u128* __restrict__ wsum,
                                                              const unsigned long long* __restrict__ psum,
-                                                             int32_t* __restrict__ next_token) {
+                                                             int32_t* __restrict__ next_token,
+                                                             int32_t* __restrict__ priv_len) {
     __shared__ u128 sh_w[kLgWaves];
     __shared__ u128 sh_base;
     __shared__ int sh_chunk;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int n = accept_len[b];
+    if (priv_len && tid == 0) priv_len[b] -= k - n;  // the rejected drafts leave the branch's KV cache
     // kLgMaxChunks = 2 * kLgThreads: every thread owns two consecutive chunk sums
     const int c0 = tid * 2;
     u128 w0 = 0, w1 = 0;
@@ -412,7 +414,8 @@ static inline bool lg_sizes_ok(int B, int k, int V) {
 
 template <bool BF16, bool VEC>
 static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float inv_temp, const int32_t* draft,
-                     const float* u, int32_t* accept_len, int32_t* next_token, void* workspace, hipStream_t s) {
+                     const float* u, int32_t* accept_len, int32_t* next_token, int32_t* priv_len, void* workspace,
+                     hipStream_t s) {
     const LgLayout l = lg_layout(B, k, V);
     float* pmax = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.off_pmax);
     unsigned long long* rsum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_rsum);
@@ -431,7 +434,7 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
     hipLaunchKernelGGL((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
-                       pmax, rsum, l.npieces, accept_len, wsum, psum, next_token);
+                       pmax, rsum, l.npieces, accept_len, wsum, psum, next_token, priv_len);
     return check_launch();
 }
 
@@ -444,8 +447,8 @@ extern "C" size_t spec_accept_logits_workspace_bytes(int32_t B, int32_t k, int32
 
 extern "C" int spec_accept_logits(int32_t B, int32_t k, int32_t V, const void* target_logits, const void* draft_logits,
                                   int32_t logit_dtype, float inv_temperature, const int32_t* draft, const float* u,
-                                  int32_t* accept_len, int32_t* next_token, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+                                  int32_t* accept_len, int32_t* next_token, int32_t* priv_len, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
     using namespace lotts;
     if (!lg_sizes_ok(B, k, V)) return LOTTS_ERR_SHAPE;
     if (logit_dtype != LOTTS_F32 && logit_dtype != LOTTS_BF16) return LOTTS_ERR_DTYPE;
@@ -462,11 +465,11 @@ extern "C" int spec_accept_logits(int32_t B, int32_t k, int32_t V, const void* t
     hipStream_t s = (hipStream_t)stream;
     if (bf16)
         return vec ? lg_launch<true, true>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
-                                           next_token, workspace, s)
+                                           next_token, priv_len, workspace, s)
                    : lg_launch<true, false>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
-                                            next_token, workspace, s);
+                                            next_token, priv_len, workspace, s);
     return vec ? lg_launch<false, true>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
-                                        next_token, workspace, s)
+                                        next_token, priv_len, workspace, s)
                : lg_launch<false, false>(B, k, V, target_logits, draft_logits, inv_temperature, draft, u, accept_len,
-                                         next_token, workspace, s);
+                                         next_token, priv_len, workspace, s);
 }

@@ -305,6 +305,40 @@ def test_accept_logits_degenerate(lotts, oracle):
     assert n_ref[0] == 2 and n_ref[1] == 0 and n_ref[2] == 1 and t_ref[2] == 100
 
 
+def test_multi_step_decode_loop_stays_on_the_device(lotts, oracle):
+    """Several verify steps enqueued back to back with no host round trip: attention over each branch's current
+    cache, acceptance from logits, and the rollback that tells the next step where each branch's cache ends.
+    Branches drift apart in length as they accept different numbers of drafts; every step is checked."""
+    cfg = BF.with_(B=6, P=96, L=640, k=3, V=5000)
+    steps = 5
+    a = S.attention_inputs(cfg)
+    d = attn_to_dev(cfg, a)
+    cache0 = np.array([10, 100, 200, 37, 0, 300], dtype=np.int32)   # valid private tokens before the first step
+    logits = [logit_inputs(cfg, 0.8, salt=s, bf16=True) for s in range(steps)]
+    print("multi-step loop", cfg, flush=True)
+    pl_dev = to_dev(cache0 + cfg.k + 1)
+    got = []
+    for s in range(steps):
+        zt, zd, draft, u = logits[s]
+        O = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], pl_dev)
+        n, t = lotts.spec_accept_logits(to_dev(zt, True), to_dev(zd, True), to_dev(draft), to_dev(u), priv_len=pl_dev)
+        got.append((O.clone(), n.clone(), t.clone(), pl_dev.clone()))
+        pl_dev += cfg.k + 1                                          # the next step appends its k + 1 new tokens
+    torch.cuda.synchronize()
+    pl = (cache0 + cfg.k + 1).astype(np.int32)
+    for s in range(steps):
+        zt, zd, draft, u = logits[s]
+        Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], pl)
+        n_ref, t_ref = oracle.spec_accept_logits(zt, zd, draft, u, priv_len=pl)
+        O, n, t, pl_after = got[s]
+        e_abs, e_fro, _ = attn_errors(O, Oref)
+        assert e_abs <= 2e-2 and e_fro <= 1e-2, (s, e_abs, e_fro)
+        assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref), s
+        assert np.array_equal(pl_after.cpu().numpy(), pl), s
+        pl = (pl + cfg.k + 1).astype(np.int32)
+    assert len(set((pl - cache0).tolist())) > 1                      # the branches did drift apart
+
+
 # ---------------------------------------------------------------------------- confidence-weighted vote
 @pytest.mark.parametrize("N,B,T", [(1, 16, 64), (5, 16, 1000), (3, 64, 37), (2, 1, 5), (2, 1024, 3)])
 def test_confidence_vote(lotts, oracle, N, B, T):

@@ -163,3 +163,31 @@ def test_decisions_recomputed_with_python_integers(oracle):
                 break
         assert t[b] == want_t
     assert (n[5:10] == 0).all()
+
+
+def test_rollback_keeps_exactly_the_verified_tokens(oracle):
+    """priv_len comes in counting the k + 1 new tokens (last emitted token + k drafts) and goes out counting the
+    tokens whose keys and values stay valid: the old cache, the last emitted token and the n accepted drafts.
+    Over a run of steps the cache therefore grows by exactly the tokens emitted (n + 1 per step)."""
+    V, k, B, steps = 60, 4, 50, 6
+    g = np.random.default_rng(12)
+    cache = g.integers(0, 500, B).astype(np.int32)          # valid private tokens before the first step
+    start = cache.copy()
+    emitted = np.zeros(B, np.int64)
+    seen = set()
+    for _ in range(steps):
+        zt = g.normal(0, 2, (B, k + 1, V)).astype(np.float32)
+        zd = (zt[:, :k] + g.normal(0, 0.8, (B, k, V))).astype(np.float32)
+        draft = np.stack([[g.choice(V, p=softmax(zd[b, j].astype(np.float64))) for j in range(k)]
+                          for b in range(B)]).astype(np.int32)
+        u = (g.integers(0, 1 << 24, (B, k + 1)) / float(1 << 24)).astype(np.float32)
+        pl = (cache + k + 1).astype(np.int32)                # what the attention of this step is given
+        n, t = oracle.spec_accept_logits(zt, zd, draft, u, priv_len=pl)
+        n0, t0 = oracle.spec_accept_logits(zt, zd, draft, u)
+        assert np.array_equal(n, n0) and np.array_equal(t, t0)   # the bookkeeping changes no decision
+        assert np.array_equal(pl, cache + 1 + n)
+        cache = pl
+        emitted += n + 1
+        seen.update(n.tolist())
+    assert np.array_equal(cache - start, emitted)
+    assert seen == set(range(k + 1))                         # every acceptance length occurred

@@ -33,7 +33,8 @@ BATTERY = {
     "vote": [TV.test_hand_cases, TV.test_against_counting_dictionary_on_zipf_answers],
     "logits": [TL.test_integer_weights_follow_two_to_the_t, lambda o: TL.test_normalised_weights_are_softmax(o, 0.7),
                TL.test_greedy_limit, TL.test_decisions_recomputed_with_python_integers,
-               TL.test_agrees_with_the_probability_path, TL.test_power_of_two_rescaling_changes_nothing],
+               TL.test_agrees_with_the_probability_path, TL.test_power_of_two_rescaling_changes_nothing,
+               TL.test_rollback_keeps_exactly_the_verified_tokens],
     "confidence": [TC.test_hand_cases, TC.test_against_dictionary, TC.test_equal_confidences_reduce_to_majority_voting],
     "gemm": [TG.test_matches_numpy_matmul, TG.test_identity_and_orientation],
 }
@@ -70,6 +71,8 @@ MUTATIONS = [
     ("logits", "a polynomial coefficient with the wrong sign", "g = fmaf(g, f, 0x1.ebfbaap-3f);", "g = fmaf(g, f, -0x1.ebfbaap-3f);"),
     ("logits", "natural exponent instead of base 2", "float t = (y - m) * 0x1.715476p+0f;", "float t = (y - m);"),
     ("logits", "temperature ignored", "return (float)load_elem(z, dtype, idx) * inv_temp;", "return (float)load_elem(z, dtype, idx);"),
+    ("logits", "rollback also drops the last accepted draft", "priv_len[b] -= k - n;", "priv_len[b] -= k - n + 1;"),
+    ("logits", "rollback drops every draft", "priv_len[b] -= k - n;", "priv_len[b] -= k;"),
     ("confidence", "min and avg exchanged", "w[b] = weight_mode == 0 ?", "w[b] = weight_mode == 1 ?"),
     ("confidence", "vote adds every branch's weight", "if (ok[j] && a[j] == a[i])\n                        score = score + w[j];",
      "if (ok[j])\n                        score = score + w[j];"),
