@@ -157,19 +157,58 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
 
-    # ---- the timed region: exactly K steps, sync on both sides.  HIP events on the launch stream
-    # bracket verify_attention calls of the region (the dominant kernel's launch duration).
+    # ---- the timed region: exactly K steps, sync on both sides.  The library's kernel timer picks out the
+    # verify_attention call of every 4th step: its launch carries its own HIP event pair on the launch
+    # stream, which reads the kernel's start and end on the device (the dominant kernel's launch
+    # duration, without the gaps that event records around a call would add).  A timed launch costs the
+    # queue about 7 us more than a plain one, hence not every step.
     K = args.steps
-    EVERY = 4   # every 4th step's verify_attention call is bracketed (an event pair costs the step ~3 us)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range((K + EVERY - 1) // EVERY)]
+    EVERY = 4
+    n_launch = ctypes.c_int32()
+    assert lib.lotts_timer_start(8) == 0
+    lib.verify_attention(*calls[0][0])
+    assert lib.lotts_timer_stop(ctypes.byref(n_launch), None) == 0
+    attn_launches = n_launch.value                     # 1, or 2 when a second launch merges the partials
+    n_timed = (K + EVERY - 1) // EVERY
+    kernel_ms = (ctypes.c_float * (n_timed * attn_launches))()
     torch.cuda.synchronize()
+    assert lib.lotts_timer_start(n_timed * attn_launches) == 0
+    lib.lotts_timer_pause(1)
     t0 = time.perf_counter()
     for i in range(K):
-        step(i, evs[i // EVERY] if i % EVERY == 0 else None)
+        if i % EVERY == 0:
+            attn_args, acc_args, vote_args = calls[i % nsets]
+            lib.lotts_timer_pause(0)
+            rc = lib.verify_attention(*attn_args)
+            lib.lotts_timer_pause(1)
+            rc |= lib.spec_accept(*acc_args)
+            rc |= lib.majority_vote(*vote_args)
+            if rc != 0:
+                raise RuntimeError("a lotts call failed (status %d)" % rc)
+        else:
+            step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    assert lib.lotts_timer_stop(ctypes.byref(n_launch), kernel_ms) == 0 and n_launch.value == n_timed * attn_launches
     ms_per_step = (t1 - t0) * 1e3 / K
-    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / len(evs)
+    attn_ms = sum(kernel_ms[0::attn_launches]) / n_timed        # attn_kernel: the launch that streams K and V
+    merge_ms = sum(kernel_ms[1::attn_launches]) / n_timed if attn_launches == 2 else 0.0
+
+    # ---- outside the timed region: the same K steps with the timer off (what the event pairs cost the step),
+    # and verify_attention calls bracketed by event records on the stream (gaps around the call included)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step_timer_off = (time.perf_counter() - t2) * 1e3 / K
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(min(K, 100))]
+    for i, e in enumerate(evs):
+        step(4 * i, e)
+        for j in range(1, 4):
+            step(4 * i + j)
+    torch.cuda.synchronize()
+    attn_ms_bracket = sum(e[0].elapsed_time(e[1]) for e in evs) / len(evs)
 
     # ---- outside the timed region: per-entry-point split, and verify_attention launched back to back
     K2 = min(K, 200)
@@ -213,13 +252,19 @@ def main() -> int:
                                "verify_attention + spec_accept + majority_vote" % (
                                    cfg.name, cfg.B, cfg.k, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, cfg.L, cfg.V),
                    "input_sets_rotated": nsets},
-        "roofline": {"bound": "hbm", "kernel": "attn_kernel (all of verify_attention: one launch)",
+        "ms_per_step_timer_off": ms_per_step_timer_off,
+        "roofline": {"bound": "hbm",
+                     "kernel": "attn_kernel (%s)" % ("all of verify_attention: one launch" if attn_launches == 1 else
+                                                     "streams K and V; attn_merge_kernel follows"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
-                     "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms, "launches_bracketed": len(evs),
-                     "avg_launch_ms_single_set_cache_resident": attn_ms_resident,
-                     "avg_launch_ms_back_to_back": attn_ms_b2b},
-        "breakdown_ms": {"verify_attention": attn_ms, "spec_accept": acc_ms, "majority_vote": vote_ms},
+                     "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms, "launches_timed": n_timed,
+                     "timing": "HIP event pair attached to the dispatch, every 4th step of the timed region",
+                     "avg_merge_launch_ms": merge_ms,
+                     "avg_call_ms_event_records_around_call": attn_ms_bracket,
+                     "avg_call_ms_single_set_cache_resident": attn_ms_resident,
+                     "avg_call_ms_back_to_back": attn_ms_b2b},
+        "breakdown_ms": {"verify_attention": attn_ms_bracket, "spec_accept": acc_ms, "majority_vote": vote_ms},
         "spec_accept": {"algorithmic_bytes": bytes_acc, "GB/s": bytes_acc / (acc_ms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": bytes_acc / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "mean_accepted": float(n0.mean()),

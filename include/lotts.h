@@ -208,6 +208,28 @@ int skinny_gemm(int32_t M, int32_t N, int32_t K, const void *X, int64_t ldx, con
                 int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Kernel timer -- device execution time of the kernels the entry points launch, for callers that
+ * have no profiler at hand (not an operation of the paper; a measurement aid).
+ * Between lotts_timer_start and lotts_timer_stop every kernel launched by the CALLING HOST THREAD
+ * through this library carries a pair of events of its own, attached to the dispatch, which read
+ * that kernel's start and end on the device; the gaps between commands are not included.
+ *   lotts_timer_start(max_launches): 1 <= max_launches <= 2^20.  Launches beyond max_launches are
+ *       not timed.  Creates the events it needs the first time (host allocation only).
+ *   lotts_timer_pause(paused): nonzero = launches are not timed until lotts_timer_pause(0); host
+ *       flag only, so single calls of a pipelined loop can be picked out without waiting for the
+ *       device (a timed launch costs the host and the queue a few microseconds more than a plain one).
+ *   lotts_timer_stop(launches, ms): waits for the timed kernels to finish, writes their number to
+ *       *launches and, if ms is not NULL, each one's milliseconds to ms[0 .. *launches), in launch
+ *       order (HOST array of at least max_launches floats).  Switches the timer off.
+ * The order of launches inside one call: verify_attention 1 (2 when the partials of a row are
+ * many: attention, then merge); spec_accept 2 (scan, pick); spec_accept_logits 4 (max, sum, scan,
+ * pick); majority_vote 1; confidence_vote 1; skinny_gemm 1 (2 when K is split: GEMM, reduce).
+ */
+int lotts_timer_start(int32_t max_launches);
+int lotts_timer_pause(int32_t paused);
+int lotts_timer_stop(int32_t *launches, float *ms);
+
+/*
  * greedy_search -- the search for the latency-optimal configuration (B*, gamma*) of Algorithm 1
  * (Section 3.3).  HOST function: it launches nothing; `tts_task(B, gamma, T, user)` is the
  * caller's evaluation of the accuracy reached with B branches and draft length gamma under the

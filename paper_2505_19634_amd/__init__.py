@@ -5,7 +5,7 @@ binding.  Importing it loads the library and fails loudly if it has not been bui
 """
 from .binding import (AttnDesc, LottsError, load, strerror, verify_attention, spec_accept,  # noqa: F401
                       spec_accept_logits, majority_vote, confidence_vote, greedy_search, skinny_gemm,
-                      make_attn_desc,
+                      make_attn_desc, kernel_timer,
                       EXPORTS, LIB_PATH)
 
 load()

@@ -18,7 +18,8 @@ LOTTS_F32, LOTTS_BF16 = 0, 1
 
 EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
            "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
-           "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "greedy_search")
+           "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "greedy_search",
+           "lotts_timer_start", "lotts_timer_pause", "lotts_timer_stop")
 
 
 class AttnDesc(ctypes.Structure):
@@ -77,6 +78,12 @@ def load() -> ctypes.CDLL:
         lib.greedy_search.argtypes = [TTS_TASK_FN, vp, ctypes.c_double, i32, i32, ctypes.POINTER(ctypes.c_int32),
                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        lib.lotts_timer_start.restype = ctypes.c_int
+        lib.lotts_timer_start.argtypes = [i32]
+        lib.lotts_timer_pause.restype = ctypes.c_int
+        lib.lotts_timer_pause.argtypes = [i32]
+        lib.lotts_timer_stop.restype = ctypes.c_int
+        lib.lotts_timer_stop.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
         lib.confidence_vote.restype = ctypes.c_int
         lib.confidence_vote.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp]
         _lib = lib
@@ -332,3 +339,31 @@ def skinny_gemm(X: torch.Tensor, W: torch.Tensor, *, out: Optional[torch.Tensor]
     if rc != 0:
         raise LottsError(rc, "skinny_gemm")
     return out
+
+
+class kernel_timer:
+    """Context manager around lotts_timer_start / lotts_timer_stop: `with kernel_timer(n) as t: ...` leaves the
+    device milliseconds of up to n kernel launches made inside, in launch order, in t.ms."""
+
+    def __init__(self, max_launches: int):
+        self.max_launches = int(max_launches)
+        self.ms = []
+
+    def __enter__(self):
+        rc = load().lotts_timer_start(self.max_launches)
+        if rc != 0:
+            raise LottsError(rc, "lotts_timer_start")
+        return self
+
+    def pause(self, paused: bool = True):
+        """Launches made while paused are not timed (and cost nothing extra)."""
+        load().lotts_timer_pause(1 if paused else 0)
+
+    def __exit__(self, *exc):
+        n = ctypes.c_int32()
+        buf = (ctypes.c_float * self.max_launches)()
+        rc = load().lotts_timer_stop(ctypes.byref(n), buf)
+        if rc != 0 and exc[0] is None:
+            raise LottsError(rc, "lotts_timer_stop")
+        self.ms = list(buf[:n.value])
+        return False

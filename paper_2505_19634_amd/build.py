@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblotts.so")
 CALIB = os.path.join(_HERE, "calib_copy")
 SOURCES = ["verify_attention.hip", "spec_accept.hip", "spec_accept_logits.hip", "majority_vote.hip",
-           "confidence_vote.hip", "skinny_gemm.hip", "greedy_search.cpp"]
+           "confidence_vote.hip", "skinny_gemm.hip", "kernel_timer.hip", "greedy_search.cpp"]
 
 
 def build(verbose: bool = False) -> str:

@@ -106,7 +106,7 @@ extern "C" int confidence_vote(int32_t N, int32_t B, int32_t T, const int32_t* a
     if (N < 1 || B < 1 || B > lotts::kConfMaxB || T < 1 || weight_mode < 0 || weight_mode > 1 || select_mode < 0 ||
         select_mode > 1)
         return LOTTS_ERR_SHAPE;
-    hipLaunchKernelGGL(lotts::confidence_vote_kernel, dim3(N), dim3(lotts::kConfThreads), 0, (hipStream_t)stream, B, T,
+    LOTTS_LAUNCH(lotts::confidence_vote_kernel, dim3(N), dim3(lotts::kConfThreads), (hipStream_t)stream, B, T,
                        answers, conf, conf_len, weight_mode, select_mode, winner, winner_score);
     return lotts::check_launch();
 }

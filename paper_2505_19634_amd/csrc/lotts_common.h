@@ -2,6 +2,7 @@
 // wavefront helpers.  gfx950 only (64-wide wavefronts).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "lotts.h"
 
@@ -12,6 +13,21 @@ constexpr int kWave = 64;
 // on the device the process happens to see, so workspace queries agree everywhere.
 constexpr int kNumCU = 256;
 constexpr int kNumXCD = 8;
+
+// Kernel timer (lotts_timer_start / lotts_timer_stop, kernel_timer.hip).  While it runs on the calling
+// host thread, timer_take hands out one pair of events per launch and the launch carries them, so
+// the pair reads that kernel's own start and end on the device.
+bool timer_take(hipEvent_t* start, hipEvent_t* stop);
+
+// Every launch of the library goes through here: no dynamic LDS, the caller's stream.
+#define LOTTS_LAUNCH(kernel, grid, block, stream, ...)                                                        \
+    do {                                                                                                      \
+        hipEvent_t lotts_e0_, lotts_e1_;                                                                      \
+        if (lotts::timer_take(&lotts_e0_, &lotts_e1_))                                                        \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, lotts_e0_, lotts_e1_, 0, __VA_ARGS__);     \
+        else                                                                                                  \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                  \
+    } while (0)
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? LOTTS_OK : LOTTS_ERR_LAUNCH;

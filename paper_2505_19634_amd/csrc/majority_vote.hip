@@ -60,7 +60,7 @@ extern "C" int majority_vote(int32_t N, int32_t B, const int32_t* answers, int32
                              void* stream) {
     if (!answers || !winner || !winner_count) return LOTTS_ERR_NULL;
     if (N < 1 || B < 1 || B > lotts::kVoteMaxB) return LOTTS_ERR_SHAPE;
-    hipLaunchKernelGGL(lotts::majority_vote_kernel, dim3(N), dim3(lotts::kVoteThreads), 0, (hipStream_t)stream, B,
+    LOTTS_LAUNCH(lotts::majority_vote_kernel, dim3(N), dim3(lotts::kVoteThreads), (hipStream_t)stream, B,
                        answers, winner, winner_count);
     return lotts::check_launch();
 }

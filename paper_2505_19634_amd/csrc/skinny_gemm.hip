@@ -34,6 +34,9 @@ struct GemmParams {
     float* part;  // [ksplit][M][N] fp32 when ksplit > 1
     int M, N, K, ksplit;
     long long ldx, ldw, ldy;
+#ifdef LOTTS_TUNING
+    int rot;
+#endif
 };
 
 struct GemmPlan {
@@ -49,6 +52,9 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     if (ks > max_ks) ks = max_ks;
     if (ks > 16) ks = 16;
     pl.ksplit = ks < 1 ? 1 : ks;
+#ifdef LOTTS_TUNING
+    if (const char* e = getenv("LOTTS_GEMM_KSPLIT")) pl.ksplit = atoi(e);
+#endif
     return pl;
 }
 
@@ -94,9 +100,16 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
+#ifdef LOTTS_TUNING
+    const int nc_ = c_hi - c_lo;
+    const int rot_ = (p.rot && nc_ > 0) ? (int)((blockIdx.x * (unsigned)p.rot) % (unsigned)nc_) : 0;
+#define CHUNK_AT(i) (c_lo + (((i) - c_lo) + rot_) % nc_)
+#else
+#define CHUNK_AT(i) (i)
+#endif
     if (c_lo < c_hi) {
-        fetch_w(c_lo);
-        fetch_x(c_lo);
+        fetch_w(CHUNK_AT(c_lo));
+        fetch_x(CHUNK_AT(c_lo));
     }
     for (int c = c_lo; c < c_hi; ++c) {
         unsigned char* xb = xbuf[(c - c_lo) & 1];
@@ -110,8 +123,8 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
         }
         __syncthreads();  // the X chunk is complete; the other buffer is free for chunk c + 1
         if (c + 1 < c_hi) {
-            fetch_w(c + 1);
-            fetch_x(c + 1);
+            fetch_w(CHUNK_AT(c + 1));
+            fetch_x(CHUNK_AT(c + 1));
         }
         // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k)
 #pragma unroll
@@ -189,8 +202,11 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     if (ldx < K || ldw < K || ldy < N || (ldx % 8) || (ldw % 8) || (ldy % 4)) return LOTTS_ERR_SHAPE;
     if ((((uintptr_t)X | (uintptr_t)W | (uintptr_t)workspace) & 15) || ((uintptr_t)Y & 7)) return LOTTS_ERR_SHAPE;
     if (workspace_bytes < skinny_gemm_workspace_bytes(M, N, K)) return LOTTS_ERR_WORKSPACE;
-    const GemmPlan pl = plan_gemm(M, N, K);
+    GemmPlan pl = plan_gemm(M, N, K);
     GemmParams p;
+#ifdef LOTTS_TUNING
+    p.rot = getenv("LOTTS_GEMM_ROT") ? atoi(getenv("LOTTS_GEMM_ROT")) : 0;
+#endif
     p.X = static_cast<const __bf16*>(X);
     p.W = static_cast<const __bf16*>(W);
     p.Y = static_cast<__bf16*>(Y);
@@ -200,14 +216,14 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     hipStream_t s = (hipStream_t)stream;
     const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads);
     switch (pl.mt) {
-        case 1: hipLaunchKernelGGL(skinny_gemm_kernel<1>, grid, block, 0, s, p); break;
-        case 2: hipLaunchKernelGGL(skinny_gemm_kernel<2>, grid, block, 0, s, p); break;
-        case 3: hipLaunchKernelGGL(skinny_gemm_kernel<3>, grid, block, 0, s, p); break;
-        default: hipLaunchKernelGGL(skinny_gemm_kernel<4>, grid, block, 0, s, p); break;
+        case 1: LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p); break;
+        case 2: LOTTS_LAUNCH(skinny_gemm_kernel<2>, grid, block, s, p); break;
+        case 3: LOTTS_LAUNCH(skinny_gemm_kernel<3>, grid, block, s, p); break;
+        default: LOTTS_LAUNCH(skinny_gemm_kernel<4>, grid, block, s, p); break;
     }
     int rc = check_launch();
     if (rc != LOTTS_OK || pl.ksplit == 1) return rc;
     const long long quads = ((long long)M * N + 3) / 4;
-    hipLaunchKernelGGL(skinny_gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, p);
+    LOTTS_LAUNCH(skinny_gemm_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), s, p);
     return check_launch();
 }

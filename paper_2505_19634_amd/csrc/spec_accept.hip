@@ -272,14 +272,14 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
     const bool vec = (V % 4 == 0) && (((uintptr_t)p & 15) == 0) && (k == 0 || ((uintptr_t)q & 15) == 0);
     const dim3 grid(pl.nchunks, B);
     if (vec)
-        hipLaunchKernelGGL(accept_scan_kernel<true>, grid, dim3(kAccThreads), 0, s, B, k, V, pl.chunk, pl.nchunks, p,
+        LOTTS_LAUNCH(accept_scan_kernel<true>, grid, dim3(kAccThreads), s, B, k, V, pl.chunk, pl.nchunks, p,
                            q, draft, u, accept_len, sums);
     else
-        hipLaunchKernelGGL(accept_scan_kernel<false>, grid, dim3(kAccThreads), 0, s, B, k, V, pl.chunk, pl.nchunks, p,
+        LOTTS_LAUNCH(accept_scan_kernel<false>, grid, dim3(kAccThreads), s, B, k, V, pl.chunk, pl.nchunks, p,
                            q, draft, u, accept_len, sums);
     int rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    hipLaunchKernelGGL(accept_pick_kernel, dim3(B), dim3(kAccThreads), 0, s, B, k, V, pl.chunk, pl.nchunks, vec, p, q, u,
+    LOTTS_LAUNCH(accept_pick_kernel, dim3(B), dim3(kAccThreads), s, B, k, V, pl.chunk, pl.nchunks, vec, p, q, u,
                        accept_len, sums, next_token);
     return check_launch();
 }

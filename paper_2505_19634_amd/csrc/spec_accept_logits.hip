@@ -422,18 +422,18 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
     u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
     unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
     const dim3 sgrid(l.npieces, B * (2 * k + 1));
-    hipLaunchKernelGGL((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), 0, s, B, k, V, l.npieces, zt, zd, inv_temp, pmax);
+    LOTTS_LAUNCH((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax);
     int rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    hipLaunchKernelGGL((lg_sum_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), 0, s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
+    LOTTS_LAUNCH((lg_sum_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
                        rsum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    hipLaunchKernelGGL((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd,
+    LOTTS_LAUNCH((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd,
                        inv_temp, draft, u, pmax, rsum, l.npieces, accept_len, wsum, psum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    hipLaunchKernelGGL((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), 0, s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
+    LOTTS_LAUNCH((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
                        pmax, rsum, l.npieces, accept_len, wsum, psum, next_token, priv_len);
     return check_launch();
 }

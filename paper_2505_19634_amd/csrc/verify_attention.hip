@@ -79,6 +79,7 @@ struct AttnParams {
     AttnPlan plan;
 #ifdef LOTTS_TUNING
     long long* dbg;  // development builds: per-workgroup phase timestamps
+    int map;
 #endif
 };
 
@@ -314,6 +315,9 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     // Order matters for latency: whatever does not depend on priv_len[b] (the prefix share, the Q
     // rows) is requested before that value is first used.
     int id = blockIdx.x;
+#ifdef LOTTS_TUNING
+    if (prm.map == 1 && (pl.n_priv_items & 7) == 0 && id < pl.n_priv_items) id = (id & 7) * (pl.n_priv_items >> 3) + (id >> 3);
+#endif
     const bool is_private = id < pl.n_priv_items;
     int kvh, split, nsplit, rho0, rho_end, slot, b_item = 0;
     KeyRun run[2];   // run[0]: folded prefix share (may be empty), run[1]: the item's own segment
@@ -612,7 +616,11 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         sh_last[tid] = last;
     }
     __syncthreads();
-    DBG_STAMP(6);
+#ifdef LOTTS_TUNING
+    if (prm.dbg && tid == 0)  // where the workgroup ran: HW_ID (register 4) and XCC_ID (register 20), read-only
+        prm.dbg[(long long)blockIdx.x * 8 + 6] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |
+                                                 ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);
+#endif
     for (int j = 0; j < nb; ++j)
         if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
     __builtin_amdgcn_s_waitcnt(0);
@@ -790,6 +798,7 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     prm.o_stride_b = d.o_stride_b; prm.o_stride_r = d.o_stride_r; prm.o_stride_h = d.o_stride_h;
 #ifdef LOTTS_TUNING
     prm.dbg = getenv("LOTTS_DBG_PTR") ? (long long*)strtoull(getenv("LOTTS_DBG_PTR"), nullptr, 0) : nullptr;
+    prm.map = getenv("LOTTS_MAP") ? atoi(getenv("LOTTS_MAP")) : 0;
 #endif
     hipStream_t s = (hipStream_t)stream;
     const long long rows = (long long)d.B * prm.R * d.Hq;
@@ -798,9 +807,9 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
         prm.plan = AttnPlan{};
         prm.ws = nullptr; prm.ws_bytes = 0; prm.off_o = prm.off_ml = 0; prm.counters = nullptr;
         if (d.D == 64)
-            hipLaunchKernelGGL(attn_f32_kernel<64>, dim3((unsigned)rows), dim3(kAttnThreads), 0, s, prm);
+            LOTTS_LAUNCH(attn_f32_kernel<64>, dim3((unsigned)rows), dim3(kAttnThreads), s, prm);
         else
-            hipLaunchKernelGGL(attn_f32_kernel<128>, dim3((unsigned)rows), dim3(kAttnThreads), 0, s, prm);
+            LOTTS_LAUNCH(attn_f32_kernel<128>, dim3((unsigned)rows), dim3(kAttnThreads), s, prm);
         return check_launch();
     }
 
@@ -816,16 +825,16 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     const long long items = (long long)pl.n_pre_items + pl.n_priv_items;
     if (items > 0x7fffffffLL) return LOTTS_ERR_SHAPE;
     const dim3 grid((unsigned)items), block(kAttnThreads);
-    if (d.D == 128 && pl.nqt == 1) hipLaunchKernelGGL((attn_kernel<128, 1>), grid, block, 0, s, prm);
-    else if (d.D == 128) hipLaunchKernelGGL((attn_kernel<128, 2>), grid, block, 0, s, prm);
-    else if (pl.nqt == 1) hipLaunchKernelGGL((attn_kernel<64, 1>), grid, block, 0, s, prm);
-    else hipLaunchKernelGGL((attn_kernel<64, 2>), grid, block, 0, s, prm);
+    if (d.D == 128 && pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<128, 1>), grid, block, s, prm);
+    else if (d.D == 128) LOTTS_LAUNCH((attn_kernel<128, 2>), grid, block, s, prm);
+    else if (pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<64, 1>), grid, block, s, prm);
+    else LOTTS_LAUNCH((attn_kernel<64, 2>), grid, block, s, prm);
     if (!pl.fused) {
         rc = check_launch();
         if (rc != LOTTS_OK) return rc;
         const dim3 mgrid((unsigned)((prm.GR * (d.D / 4) + kAttnThreads - 1) / kAttnThreads), (unsigned)(d.Hkv * d.B));
-        if (d.D == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, block, 0, s, prm);
-        else hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, block, 0, s, prm);
+        if (d.D == 128) LOTTS_LAUNCH(attn_merge_kernel<128>, mgrid, block, s, prm);
+        else LOTTS_LAUNCH(attn_merge_kernel<64>, mgrid, block, s, prm);
     }
     return check_launch();
 }

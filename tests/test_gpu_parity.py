@@ -392,3 +392,42 @@ def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle):
     assert torch.equal(Y1, Y2) and float(out[:, N:].abs().sum()) == 0.0
     ref = oracle.skinny_gemm(X.contiguous().view(torch.uint16).cpu().numpy(), W.contiguous().view(torch.uint16).cpu().numpy())
     assert np.linalg.norm(Y1.float().cpu().numpy() - ref) / np.linalg.norm(ref) <= 3e-3
+
+
+# ---------------------------------------------------------------------------- kernel timer
+def test_kernel_timer_counts_launches_and_changes_no_result(lotts, oracle):
+    """Launches made while the timer runs carry their own events: the count per entry point is the documented
+    one, every duration is positive and shorter than the host-side bracket around it, outputs are untouched,
+    and launches after the timer is full or stopped run untimed."""
+    import time
+    cfg = BF.with_(B=16, P=128, L=500)                   # 128 (head, branch) pairs: two partials per row, merged in the launch
+    d = attn_to_dev(cfg, S.attention_inputs(cfg))
+    s = S.accept_inputs(S.CONFIGS["C2"].with_(B=4, V=30000))
+    sd = {n: to_dev(s[n]) for n in ("p", "q", "draft", "u")}
+    votes = to_dev(S.vote_inputs(cfg))
+    attn = lambda: lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    O0 = attn().clone()
+    n0, t0 = [x.clone() for x in lotts.spec_accept(sd["p"], sd["q"], sd["draft"], sd["u"])]
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    with lotts.kernel_timer(16) as t:
+        O1 = attn().clone()
+        n1, t1 = lotts.spec_accept(sd["p"], sd["q"], sd["draft"], sd["u"])
+        lotts.majority_vote(votes)
+    wall_ms = (time.perf_counter() - c0) * 1e3        # the exit waited for the kernels
+    assert len(t.ms) == 1 + 2 + 1, t.ms                  # this attention plan merges inside its one launch
+    assert all(0.0 < v < wall_ms for v in t.ms), (t.ms, wall_ms)
+    assert torch.equal(O0, O1) and torch.equal(n0, n1) and torch.equal(t0, t1)
+    with lotts.kernel_timer(1) as t:                     # full after one launch: the rest is simply not timed
+        O2 = attn()
+        lotts.majority_vote(votes)
+    assert len(t.ms) == 1 and torch.equal(O0, O2)
+    with lotts.kernel_timer(4) as t:
+        pass
+    assert t.ms == []
+    few = BF.with_(B=2, Hq=16, Hkv=2, k=2, P=64, L=4000)   # few pairs: many partials per row, a second launch merges
+    d2 = attn_to_dev(few, S.attention_inputs(few))
+    with lotts.kernel_timer(4) as t:
+        lotts.verify_attention(d2["Q"], d2["Kpre"], d2["Vpre"], d2["Kpriv"], d2["Vpriv"], d2["priv_len"])
+    assert len(t.ms) == 2 and min(t.ms) > 0.0
+    assert torch.equal(O0, attn())                       # timer off again
