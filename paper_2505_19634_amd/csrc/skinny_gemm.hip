@@ -5,7 +5,7 @@
 //
 //   skinny_gemm_kernel<MT>  grid (blocks of 128 weight rows, K splits).  Each of the 4 wavefronts owns 32
 //       weight rows and walks the K range in chunks of 128: the W tile (32 x 128, 8 KB) comes in with
-//       coalesced non-temporal 16-byte loads one chunk ahead, is staged through a wavefront-private LDS
+//       coalesced non-temporal 16-byte loads two chunks ahead, is staged through a wavefront-private LDS
 //       slab and read back as the MFMA A operand; the X chunk (up to 128 x 128) is fetched once per
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
@@ -27,6 +27,7 @@ constexpr int kGemmBlockN = kGemmWaves * kGemmRows;   // weight rows per workgro
 constexpr int kGemmChunk = 128;                       // K elements per chunk
 constexpr int kGemmRowBytes = kGemmChunk * 2 + 16;    // LDS row pitch: conflict-free 16-byte row reads
 constexpr int kGemmMaxM = 128;
+constexpr int kGemmMaxSplit = 32;
 
 struct GemmParams {
     const __bf16 *X, *W;
@@ -34,9 +35,6 @@ struct GemmParams {
     float* part;  // [ksplit][M][N] fp32 when ksplit > 1
     int M, N, K, ksplit;
     long long ldx, ldw, ldy;
-#ifdef LOTTS_TUNING
-    int rot;
-#endif
 };
 
 struct GemmPlan {
@@ -47,10 +45,18 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     pl.mt = (M + 31) / 32;
     pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
     const int chunks = K / kGemmChunk;
-    int ks = (kNumCU + pl.nblocks - 1) / pl.nblocks;  // about one workgroup per compute unit
-    const int max_ks = chunks / 4 > 0 ? chunks / 4 : 1;
-    if (ks > max_ks) ks = max_ks;
-    if (ks > 16) ks = 16;
+    // Few weight rows: split K so that the launch fills the chip.  Measured on the 32B-shaped layers:
+    // a workgroup count just above the number of compute units is the worst choice (a few units run
+    // two workgroups and everybody waits for them), so the count stays at or below one per unit --
+    // or, when every workgroup still gets a long run of chunks, at or below two per unit.
+    int ks = 1;
+    if (pl.nblocks < kNumCU) {
+        ks = (2 * kNumCU) / pl.nblocks;
+        if (chunks / ks < 16) ks = kNumCU / pl.nblocks;
+        const int max_ks = chunks / 4 > 0 ? chunks / 4 : 1;  // at least 4 chunks per workgroup
+        if (ks > max_ks) ks = max_ks;
+        if (ks > kGemmMaxSplit) ks = kGemmMaxSplit;
+    }
     pl.ksplit = ks < 1 ? 1 : ks;
 #ifdef LOTTS_TUNING
     if (const char* e = getenv("LOTTS_GEMM_KSPLIT")) pl.ksplit = atoi(e);
@@ -73,13 +79,14 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
 
     // W tile: 8 load instructions, each covering 4 whole 256-byte row pieces
     const int w_row = lane >> 4, w_ch = lane & 15;
-    g_u32x4 wst[8];
-    auto fetch_w = [&](int c) {
+    constexpr int NPF = 2;  // W chunks in flight ahead of the one being multiplied (16 KB per wavefront)
+    g_u32x4 wst[NPF][8];
+    auto fetch_w = [&](int c, g_u32x4 (&dst)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             int n = n0 + i * 4 + w_row;
             n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
-            wst[i] = __builtin_nontemporal_load(
+            dst[i] = __builtin_nontemporal_load(
                 reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
         }
     };
@@ -100,32 +107,26 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-#ifdef LOTTS_TUNING
-    const int nc_ = c_hi - c_lo;
-    const int rot_ = (p.rot && nc_ > 0) ? (int)((blockIdx.x * (unsigned)p.rot) % (unsigned)nc_) : 0;
-#define CHUNK_AT(i) (c_lo + (((i) - c_lo) + rot_) % nc_)
-#else
-#define CHUNK_AT(i) (i)
-#endif
     if (c_lo < c_hi) {
-        fetch_w(CHUNK_AT(c_lo));
-        fetch_x(CHUNK_AT(c_lo));
+        fetch_w(c_lo, wst[0]);
+        fetch_x(c_lo);
     }
+    if (c_lo + 1 < c_hi) fetch_w(c_lo + 1, wst[1]);
     for (int c = c_lo; c < c_hi; ++c) {
         unsigned char* xb = xbuf[(c - c_lo) & 1];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
+            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[0][i];
 #pragma unroll
         for (int i = 0; i < 2 * MT; ++i) {
             const int idx = tid + i * kGemmThreads;
             *reinterpret_cast<g_u32x4*>(xb + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
         }
         __syncthreads();  // the X chunk is complete; the other buffer is free for chunk c + 1
-        if (c + 1 < c_hi) {
-            fetch_w(CHUNK_AT(c + 1));
-            fetch_x(CHUNK_AT(c + 1));
-        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wst[0][i] = wst[1][i];
+        if (c + 2 < c_hi) fetch_w(c + 2, wst[1]);
+        if (c + 1 < c_hi) fetch_x(c + 1);
         // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k)
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -204,9 +205,7 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     if (workspace_bytes < skinny_gemm_workspace_bytes(M, N, K)) return LOTTS_ERR_WORKSPACE;
     GemmPlan pl = plan_gemm(M, N, K);
     GemmParams p;
-#ifdef LOTTS_TUNING
-    p.rot = getenv("LOTTS_GEMM_ROT") ? atoi(getenv("LOTTS_GEMM_ROT")) : 0;
-#endif
+
     p.X = static_cast<const __bf16*>(X);
     p.W = static_cast<const __bf16*>(W);
     p.Y = static_cast<__bf16*>(Y);

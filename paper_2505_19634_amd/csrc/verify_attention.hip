@@ -79,7 +79,6 @@ struct AttnParams {
     AttnPlan plan;
 #ifdef LOTTS_TUNING
     long long* dbg;  // development builds: per-workgroup phase timestamps
-    int map;
 #endif
 };
 
@@ -315,9 +314,6 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     // Order matters for latency: whatever does not depend on priv_len[b] (the prefix share, the Q
     // rows) is requested before that value is first used.
     int id = blockIdx.x;
-#ifdef LOTTS_TUNING
-    if (prm.map == 1 && (pl.n_priv_items & 7) == 0 && id < pl.n_priv_items) id = (id & 7) * (pl.n_priv_items >> 3) + (id >> 3);
-#endif
     const bool is_private = id < pl.n_priv_items;
     int kvh, split, nsplit, rho0, rho_end, slot, b_item = 0;
     KeyRun run[2];   // run[0]: folded prefix share (may be empty), run[1]: the item's own segment
@@ -431,7 +427,11 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         run[1].V = (const __bf16*)prm.Vpre + (long long)kvh * prm.kpre_stride_h;
         run[1].stride_t = prm.kpre_stride_t;
     }
-    run[1].lo = wave_of_seg * kTile;
+    // The dealing goes on where the folded prefix tiles stopped: prefix and private tiles form one
+    // sequence, so a wavefront that got one prefix tile more gets one private tile less.
+    int first_wave = 0;
+    if (is_private && pl.fold) first_wave = ((prm.P + kTile - 1) / kTile) % waves_of_seg;
+    run[1].lo = ((wave_of_seg - first_wave + waves_of_seg) % waves_of_seg) * kTile;
     run[1].hi = seg_len;
     run[1].step = waves_of_seg * kTile;
     run[1].ntiles = run[1].lo < seg_len ? (seg_len - run[1].lo + run[1].step - 1) / run[1].step : 0;
@@ -798,7 +798,6 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     prm.o_stride_b = d.o_stride_b; prm.o_stride_r = d.o_stride_r; prm.o_stride_h = d.o_stride_h;
 #ifdef LOTTS_TUNING
     prm.dbg = getenv("LOTTS_DBG_PTR") ? (long long*)strtoull(getenv("LOTTS_DBG_PTR"), nullptr, 0) : nullptr;
-    prm.map = getenv("LOTTS_MAP") ? atoi(getenv("LOTTS_MAP")) : 0;
 #endif
     hipStream_t s = (hipStream_t)stream;
     const long long rows = (long long)d.B * prm.R * d.Hq;
