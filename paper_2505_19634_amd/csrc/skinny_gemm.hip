@@ -79,8 +79,9 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
 
     // W tile: 8 load instructions, each covering 4 whole 256-byte row pieces
     const int w_row = lane >> 4, w_ch = lane & 15;
-    constexpr int NPF = 2;  // W chunks in flight ahead of the one being multiplied (16 KB per wavefront)
-    g_u32x4 wst[NPF][8];
+    // Two W chunks are in flight per wavefront (16 KB), in two register sets that take turns: a set is
+    // refilled with chunk c + 2 as soon as chunk c has been copied from it into the LDS slab.
+    g_u32x4 w_even[8], w_odd[8];
     auto fetch_w = [&](int c, g_u32x4 (&dst)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -91,8 +92,8 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
         }
     };
     // X chunk: XROWS rows x 16 pieces of 16 bytes, 2 * MT pieces per thread
-    g_u32x4 xst[2 * MT];
-    auto fetch_x = [&](int c) {
+    g_u32x4 x_even[2 * MT], x_odd[2 * MT];
+    auto fetch_x = [&](int c, g_u32x4 (&xst)[2 * MT]) {
 #pragma unroll
         for (int i = 0; i < 2 * MT; ++i) {
             const int idx = tid + i * kGemmThreads;
@@ -107,16 +108,11 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    if (c_lo < c_hi) {
-        fetch_w(c_lo, wst[0]);
-        fetch_x(c_lo);
-    }
-    if (c_lo + 1 < c_hi) fetch_w(c_lo + 1, wst[1]);
-    for (int c = c_lo; c < c_hi; ++c) {
+    // One chunk.  Loads complete in issue order and every chunk's X piece is issued before its W piece,
+    // so the barrier (X staged by all four wavefronts) never waits for anybody's W data: each wavefront
+    // waits for its own W chunk after the barrier and the four drift apart by up to one chunk.
+    auto chunk = [&](int c, g_u32x4 (&w)[8], g_u32x4 (&xst)[2 * MT]) {
         unsigned char* xb = xbuf[(c - c_lo) & 1];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[0][i];
 #pragma unroll
         for (int i = 0; i < 2 * MT; ++i) {
             const int idx = tid + i * kGemmThreads;
@@ -124,9 +120,12 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
         }
         __syncthreads();  // the X chunk is complete; the other buffer is free for chunk c + 1
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wst[0][i] = wst[1][i];
-        if (c + 2 < c_hi) fetch_w(c + 2, wst[1]);
-        if (c + 1 < c_hi) fetch_x(c + 1);
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = w[i];
+        if (c + 2 < c_hi) {
+            fetch_x(c + 2, xst);
+            fetch_w(c + 2, w);
+        }
         // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k)
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -138,6 +137,18 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
             }
         }
+    };
+    if (c_lo < c_hi) {
+        fetch_x(c_lo, x_even);
+        fetch_w(c_lo, w_even);
+    }
+    if (c_lo + 1 < c_hi) {
+        fetch_x(c_lo + 1, x_odd);
+        fetch_w(c_lo + 1, w_odd);
+    }
+    for (int c = c_lo; c < c_hi; c += 2) {
+        chunk(c, w_even, x_even);
+        if (c + 1 < c_hi) chunk(c + 1, w_odd, x_odd);
     }
     // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
 #pragma unroll
