@@ -3,7 +3,7 @@
 // Section 3.2: B branches of one question; Section 2: the target model verifies the drafts in
 // one parallel forward; Section 3.1: the step is bound by loading the KV cache).
 //
-// bf16 path (MFMA, gfx950), ONE launch:
+// bf16 path (MFMA, gfx950), normally ONE launch:
 //   attn_kernel           one launch over "work items", one 4-wavefront workgroup each.  An item
 //       is a share of the keys of one KV segment and a stack of up to 32*NQT query rows that all
 //       read those keys:
@@ -16,8 +16,9 @@
 //           each private item first runs its share of the prefix keys for its own rows (served by
 //           the L2 after the first touch, so HBM still sees the prefix once) and continues into
 //           the private keys with the same running state -- no extra partial, no extra workgroups.
-//       Each wavefront streams a contiguous run of keys in 32-key tiles: coalesced non-temporal
-//       16-byte loads into registers one tile ahead, staged through a wavefront-private LDS slab
+//       The 32-key tiles of a segment are dealt round-robin to all wavefronts working on it; a
+//       wavefront streams its tiles with coalesced non-temporal 16-byte loads into registers one
+//       tile ahead, staged through a wavefront-private LDS slab
 //       (K read back row-wise as the MFMA A operand, V with the transposing LDS load), S^T = K Q^T
 //       and O^T += V^T P^T on 32x32x16 bf16 MFMA, flash-style running (max, sum, O).  The 4 states
 //       are combined through LDS after one barrier and the item's un-normalised partial goes to
@@ -27,6 +28,9 @@
 //       each with its own L2 -- inside one launch, so they are written and read with 16-byte
 //       buffer accesses that carry the device-scope cache policy (performed at the memory side of
 //       the L2s); nothing is ever flushed or invalidated cache-wide.
+//   attn_merge_kernel     second launch, only when a row has many partials (few branches or long
+//       caches): one workgroup would merge them at one compute unit's bandwidth, so the merge is
+//       spread over the chip instead.
 // fp32 path: attn_f32_kernel, plain fp32 VALU arithmetic, one workgroup per output row; it
 // exists for exactness checks on small fp32 problems, not for speed.
 #include <cstdlib>

@@ -431,3 +431,49 @@ def test_kernel_timer_counts_launches_and_changes_no_result(lotts, oracle):
         lotts.verify_attention(d2["Q"], d2["Kpre"], d2["Vpre"], d2["Kpriv"], d2["Vpriv"], d2["priv_len"])
     assert len(t.ms) == 2 and min(t.ms) > 0.0
     assert torch.equal(O0, attn())                       # timer off again
+
+
+# ---------------------------------------------------------------------------- HIP graph capture
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(lotts, oracle):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no host
+    synchronisation), so a whole step can be captured.  The graph is replayed several times with eager work
+    and synchronisations in between, on changing inputs, and every replay must equal the eager result."""
+    cfg = BF.with_(B=16, P=128, L=600, V=30000)
+    a = S.attention_inputs(cfg)
+    d = attn_to_dev(cfg, a)
+    s = S.accept_inputs(cfg)
+    sd = {n: to_dev(s[n]) for n in ("p", "q", "draft", "u")}
+    votes = to_dev(S.vote_inputs(cfg))
+    O = torch.empty_like(d["Q"])
+    n = torch.empty((cfg.B,), dtype=torch.int32, device=DEV)
+    t = torch.empty((cfg.B,), dtype=torch.int32, device=DEV)
+
+    def step(stream=None):
+        lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"], out=O, stream=stream)
+        lotts.spec_accept(sd["p"], sd["q"], sd["draft"], sd["u"], accept_len=n, next_token=t, stream=stream)
+        return lotts.majority_vote(votes, stream=stream)
+
+    w_eager, c_eager = step()                              # also creates the cached workspaces outside the capture
+    torch.cuda.synchronize()
+    Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
+    e_abs, e_fro, _ = attn_errors(O, Oref)
+    assert e_abs <= 2e-2 and e_fro <= 1e-2
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        w_g, c_g = step(torch.cuda.current_stream())
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    for rep in range(4):
+        if rep > 0:                                        # new inputs in the same buffers
+            d["Q"].copy_((torch.randn(d["Q"].shape, generator=gen, device=DEV) * 0.5).to(torch.bfloat16))
+            sd["u"].copy_(torch.randint(0, 1 << 24, sd["u"].shape, generator=gen, device=DEV).float() / float(1 << 24))
+        step()
+        torch.cuda.synchronize()
+        want = (O.clone(), n.clone(), t.clone())
+        O.zero_(); n.fill_(-7); t.fill_(-7); w_g.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, want[0]) and torch.equal(n, want[1]) and torch.equal(t, want[2]), rep
+        assert torch.equal(w_g, w_eager) and torch.equal(c_g, c_eager)
