@@ -14,8 +14,9 @@
 //
 // Four launches:
 //   lg_max_kernel, lg_sum_kernel   grid (pieces of 16384 logits, B * (2k + 1) rows): piece maxima, then --
-//                       with the row maximum known -- the pieces' integer weight sums; the second sweep
-//                       of the logits is served by the L2 / memory-side cache.
+//                       with the row maximum known -- the pieces' integer weight sums, added into one
+//                       64-bit sum per row with device-scope atomics (integers: any order gives the same
+//                       sum); the second sweep of the logits is served by the L2 / memory-side cache.
 //   lg_scan_kernel      grid (chunks, B): accept tests -> n; 128-bit chunk sums of the weights of row n.
 //   lg_pick_kernel      grid (B): chunk and token where the integer CDF crosses the threshold.
 #include "lotts_common.h"
@@ -55,13 +56,14 @@ __device__ __forceinline__ float pow2_neg_poly(float f) {
 // (the weight is at most 2^30, so the conversion is a 32-bit one)
 __device__ __forceinline__ unsigned logit_weight(float y, float m) {
     const float t = __fmul_rn(__fsub_rn(y, m), 0x1.715476p+0f);
-    const float a = -t;
+    // -t clamped to 31 (also for -inf logits and NaN from a row that is -inf throughout: fminf returns
+    // the other operand): from 31 on the weight truncates to 0 by itself, P(0) * 2^-1 = 0.5, so the
+    // definition's "0 when floor(-t) >= 31" needs no branch and no select
+    const float a = fminf(-t, 31.0f);
     const float nf = floorf(a);
-    if (!(nf < 31.0f)) return 0u;
     const float f = __fsub_rn(a, nf);
     const float g = pow2_neg_poly(f);
-    const float scale = __uint_as_float((unsigned)(127 + 30 - (int)nf) << 23);  // 2^(30 - n), exact
-    return __float2uint_rz(__fmul_rn(g, scale));
+    return __float2uint_rz(ldexpf(g, 30 - (int)nf));  // g * 2^(30 - n): exact scaling, then truncation
 }
 
 template <bool BF16>
@@ -88,6 +90,52 @@ __device__ __forceinline__ void load_y8(const void* z, size_t idx, float inv_tem
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i) y[i] = __fmul_rn(v[i], inv_temp);
+    }
+}
+
+// A thread's share of one piece of kLgPiece logits: kLgPieceIters groups of 8 consecutive logits, all
+// requested before the first is used (one 16-byte load per group would otherwise wait for the one
+// before it, and the sweep would run at the memory latency instead of the bandwidth).  Groups past
+// the end of the row read as -inf.
+constexpr int kLgPieceIters = kLgPiece / (kLgThreads * 8);
+template <bool BF16>
+__device__ __forceinline__ void load_piece(const void* z, size_t base, int lo, int hi, int tid, float inv_temp,
+                                           float (&y)[kLgPieceIters][8]) {
+    if (BF16) {
+        uint4 raw[kLgPieceIters];
+#pragma unroll
+        for (int it = 0; it < kLgPieceIters; ++it) {
+            const int i = lo + (it * kLgThreads + tid) * 8;
+            raw[it] = make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);  // bf16 -inf
+            if (i < hi) raw[it] = *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(z) + base + i);
+        }
+#pragma unroll
+        for (int it = 0; it < kLgPieceIters; ++it) {
+            const unsigned w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                y[it][2 * e] = __fmul_rn(__uint_as_float(w[e] << 16), inv_temp);
+                y[it][2 * e + 1] = __fmul_rn(__uint_as_float(w[e] & 0xffff0000u), inv_temp);
+            }
+        }
+    } else {
+        float4 raw[kLgPieceIters][2];
+#pragma unroll
+        for (int it = 0; it < kLgPieceIters; ++it) {
+            const int i = lo + (it * kLgThreads + tid) * 8;
+            raw[it][0] = raw[it][1] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (i < hi) {
+                raw[it][0] = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + base + i);
+                raw[it][1] = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + base + i + 4);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < kLgPieceIters; ++it) {
+            const float v[8] = {raw[it][0].x, raw[it][0].y, raw[it][0].z, raw[it][0].w,
+                                raw[it][1].x, raw[it][1].y, raw[it][1].z, raw[it][1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[it][e] = __fmul_rn(v[e], inv_temp);
+        }
     }
 }
 
@@ -143,7 +191,8 @@ __device__ __forceinline__ int drow(int B, int b, int j, int k) { return B * (k 
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kLgThreads) void lg_max_kernel(int B, int k, int V, int npieces, const void* __restrict__ zt,
                                                             const void* __restrict__ zd, float inv_temp,
-                                                            float* __restrict__ pmax) {
+                                                            float* __restrict__ pmax,
+                                                            unsigned long long* __restrict__ rsum) {
     __shared__ float sh_m[kLgWaves];
     const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
     const int nt = B * (k + 1);
@@ -152,12 +201,12 @@ __global__ __launch_bounds__(kLgThreads) void lg_max_kernel(int B, int k, int V,
     const int lo = pc * kLgPiece, hi = min(V, lo + kLgPiece);
     float m = -INFINITY;
     if (VEC) {
-        for (int i = lo + tid * 8; i < hi; i += kLgThreads * 8) {
-            float y[8];
-            load_y8<BF16>(z, base + i, inv_temp, y);
+        float y[kLgPieceIters][8];
+        load_piece<BF16>(z, base, lo, hi, tid, inv_temp, y);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) m = fmaxf(m, y[e]);
-        }
+        for (int it = 0; it < kLgPieceIters; ++it)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m = fmaxf(m, y[it][e]);
     } else {
         for (int i = lo + tid; i < hi; i += kLgThreads) m = fmaxf(m, load_y<BF16>(z, base + i, inv_temp));
     }
@@ -169,21 +218,31 @@ __global__ __launch_bounds__(kLgThreads) void lg_max_kernel(int B, int k, int V,
 #pragma unroll
         for (int w = 1; w < kLgWaves; ++w) m = fmaxf(m, sh_m[w]);
         pmax[(size_t)r * npieces + pc] = m;
+        if (pc == 0) rsum[r] = 0ull;  // lg_sum_kernel adds the pieces' sums into it
     }
 }
 
-// maximum of a row from its piece maxima (npieces <= 64: one value per lane at most)
+// Row maximum from the per-piece maxima.  The piece values are read in
+// blocks of 16 independent loads: a plain loop would wait for every load before issuing the next and
+// spend one memory latency per piece.
 __device__ __forceinline__ float row_max(const float* pmax, int row, int npieces) {
     float m = -INFINITY;
-    for (int i = 0; i < npieces; ++i) m = fmaxf(m, pmax[(size_t)row * npieces + i]);
+    const float* src = pmax + (size_t)row * npieces;
+    for (int i0 = 0; i0 < npieces; i0 += 16) {
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = src[min(i0 + e, npieces - 1)];  // repeats of the last piece do no harm
+#pragma unroll
+        for (int e = 0; e < 16; ++e) m = fmaxf(m, v[e]);
+    }
     return m;
 }
-__device__ __forceinline__ RowStat row_stat(const float* pmax, const unsigned long long* psum_row, int row, int npieces) {
+// final statistics of a row, as lg_sum_kernel leaves them
+__device__ __forceinline__ RowStat row_stat(const float* rmax, const unsigned long long* rsum, int row) {
     RowStat st;
-    st.m = row_max(pmax, row, npieces);
+    st.S = rsum[row];
     st.pad = 0.f;
-    st.S = 0;
-    for (int i = 0; i < npieces; ++i) st.S += psum_row[(size_t)row * npieces + i];
+    st.m = rmax[row];
     return st;
 }
 
@@ -191,6 +250,7 @@ template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V, int npieces, const void* __restrict__ zt,
                                                             const void* __restrict__ zd, float inv_temp,
                                                             const float* __restrict__ pmax,
+                                                            float* __restrict__ rmax,
                                                             unsigned long long* __restrict__ rsum) {
     __shared__ unsigned long long sh_s[kLgWaves];
     const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
@@ -201,12 +261,13 @@ __global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V,
     const float m = row_max(pmax, r, npieces);
     unsigned long long s = 0;
     if (VEC) {
-        for (int i = lo + tid * 8; i < hi; i += kLgThreads * 8) {
-            float y[8];
-            load_y8<BF16>(z, base + i, inv_temp, y);
+        float y[kLgPieceIters][8];
+        load_piece<BF16>(z, base, lo, hi, tid, inv_temp, y);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += logit_weight(y[e], m);
-        }
+        for (int it = 0; it < kLgPieceIters; ++it)
+#pragma unroll
+            for (int e = 0; e < 8; e += 2)  // two weights (each at most 2^30) fit 32 bits together
+                s += logit_weight(y[it][e], m) + logit_weight(y[it][e + 1], m);
     } else {
         for (int i = lo + tid; i < hi; i += kLgThreads) s += logit_weight(load_y<BF16>(z, base + i, inv_temp), m);
     }
@@ -217,7 +278,8 @@ __global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V,
         unsigned long long tot = 0;
 #pragma unroll
         for (int w = 0; w < kLgWaves; ++w) tot += sh_s[w];
-        rsum[(size_t)r * npieces + pc] = tot;
+        atomicAdd(&rsum[r], tot);  // integers: the order of the pieces cannot matter
+        if (pc == 0) rmax[r] = m;   // the row maximum, for the launches that follow
     }
 }
 
@@ -225,15 +287,14 @@ __global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V,
 template <bool BF16>
 __device__ __forceinline__ int lg_accepted_length(int B, int b, int k, int V, const void* zt, const void* zd,
                                                   float inv_temp, const int32_t* draft, const float* u,
-                                                  const float* pmax, const unsigned long long* rsum, int npieces,
-                                                  int* sh_first) {
+                                                  const float* rmax, const unsigned long long* rsum, int* sh_first) {
     const int tid = threadIdx.x;
     bool rejected = false;
     if (tid < k) {
         int x = draft[(size_t)b * k + tid];
         x = x < 0 ? 0 : (x >= V ? V - 1 : x);
-        const RowStat sp = row_stat(pmax, rsum, trow(b, tid, k), npieces);
-        const RowStat sq = row_stat(pmax, rsum, drow(B, b, tid, k), npieces);
+        const RowStat sp = row_stat(rmax, rsum, trow(b, tid, k));
+        const RowStat sq = row_stat(rmax, rsum, drow(B, b, tid, k));
         const unsigned long long Ep = logit_weight(load_y<BF16>(zt, (size_t)trow(b, tid, k) * V + x, inv_temp), sp.m);
         const unsigned long long Eq = logit_weight(load_y<BF16>(zd, ((size_t)b * k + tid) * V + x, inv_temp), sq.m);
         const u128 U = (u128)(unsigned)(u[(size_t)b * (k + 1) + tid] * 16777216.0f);
@@ -284,21 +345,21 @@ __global__ __launch_bounds__(kLgThreads) void lg_scan_kernel(int B, int k, int V
                                                              const void* __restrict__ zd, float inv_temp,
                                                              const int32_t* __restrict__ draft,
                                                              const float* __restrict__ u,
-                                                             const float* __restrict__ pmax,
-                                                             const unsigned long long* __restrict__ rsum, int npieces,
+                                                             const float* __restrict__ rmax,
+                                                             const unsigned long long* __restrict__ rsum,
                                                              int32_t* __restrict__ accept_len, u128* __restrict__ wsum,
                                                              unsigned long long* __restrict__ psum) {
     __shared__ int sh_first[kLgWaves];
     __shared__ u128 sh_w[kLgWaves];
     const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
-    const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, pmax, rsum, npieces, sh_first);
+    const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, rmax, rsum, sh_first);
     if (c == 0 && tid == 0) accept_len[b] = n;
     const bool residual = n < k;
     const size_t es = BF16 ? 2 : 4;
     const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
     const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
-    const RowStat sp = row_stat(pmax, rsum, trow(b, n, k), npieces);
-    const RowStat sq = residual ? row_stat(pmax, rsum, drow(B, b, n, k), npieces) : sp;
+    const RowStat sp = row_stat(rmax, rsum, trow(b, n, k));
+    const RowStat sq = residual ? row_stat(rmax, rsum, drow(B, b, n, k)) : sp;
     u128 W[8];
     unsigned long long Ep[8];
     lg_weights8<BF16, VEC>(zt_row, zd_row, c * kLgChunk + tid * 8, V, inv_temp, residual, sp, sq, W, Ep);
@@ -320,8 +381,8 @@ template <bool BF16, bool VEC>
 __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
                                                              const void* __restrict__ zd, float inv_temp,
                                                              const float* __restrict__ u,
-                                                             const float* __restrict__ pmax,
-                                                             const unsigned long long* __restrict__ rsum, int npieces,
+                                                             const float* __restrict__ rmax,
+                                                             const unsigned long long* __restrict__ rsum,
                                                              const int32_t* __restrict__ accept_len,
                                                              const u128* __restrict__ wsum,
                                                              const unsigned long long* __restrict__ psum,
@@ -368,8 +429,8 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
     const size_t es = BF16 ? 2 : 4;
     const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
     const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
-    const RowStat sp = row_stat(pmax, rsum, trow(b, n, k), npieces);
-    const RowStat sq = residual ? row_stat(pmax, rsum, drow(B, b, n, k), npieces) : sp;
+    const RowStat sp = row_stat(rmax, rsum, trow(b, n, k));
+    const RowStat sq = residual ? row_stat(rmax, rsum, drow(B, b, n, k)) : sp;
     u128 W[8];
     unsigned long long Ep[8];
     const int lo = c * kLgChunk + tid * 8;
@@ -392,7 +453,7 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
 }
 
 struct LgLayout {
-    size_t off_pmax, off_rsum, off_wsum, off_psum, total;
+    size_t off_pmax, off_rmax, off_rsum, off_wsum, off_psum, total;
     int nchunks, npieces;
 };
 static inline LgLayout lg_layout(int B, int k, int V) {
@@ -402,8 +463,9 @@ static inline LgLayout lg_layout(int B, int k, int V) {
     const size_t rows = (size_t)B * (2 * k + 1);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     l.off_pmax = 0;
-    l.off_rsum = up(rows * l.npieces * sizeof(float));
-    l.off_wsum = l.off_rsum + up(rows * l.npieces * sizeof(unsigned long long));
+    l.off_rmax = up(rows * l.npieces * sizeof(float));
+    l.off_rsum = l.off_rmax + up(rows * sizeof(float));
+    l.off_wsum = l.off_rsum + up(rows * sizeof(unsigned long long));
     l.off_psum = l.off_wsum + up((size_t)B * l.nchunks * sizeof(u128));
     l.total = l.off_psum + up((size_t)B * l.nchunks * sizeof(unsigned long long));
     return l;
@@ -418,23 +480,25 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
                      hipStream_t s) {
     const LgLayout l = lg_layout(B, k, V);
     float* pmax = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.off_pmax);
+    float* rmax = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.off_rmax);
     unsigned long long* rsum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_rsum);
     u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
     unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
     const dim3 sgrid(l.npieces, B * (2 * k + 1));
-    LOTTS_LAUNCH((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax);
+    LOTTS_LAUNCH((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
+                 rsum);
     int rc = check_launch();
     if (rc != LOTTS_OK) return rc;
     LOTTS_LAUNCH((lg_sum_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
-                       rsum);
+                 rmax, rsum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
     LOTTS_LAUNCH((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd,
-                       inv_temp, draft, u, pmax, rsum, l.npieces, accept_len, wsum, psum);
+                       inv_temp, draft, u, rmax, rsum, accept_len, wsum, psum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
     LOTTS_LAUNCH((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
-                       pmax, rsum, l.npieces, accept_len, wsum, psum, next_token, priv_len);
+                       rmax, rsum, accept_len, wsum, psum, next_token, priv_len);
     return check_launch();
 }
 
