@@ -271,6 +271,24 @@ def main() -> int:
                         "emitted_tokens_per_s": float((n0 + 1).sum()) / (ms_per_step * 1e-3)},
     }
 
+    def time_op(call, reps, launches_per_call):
+        """(average ms of the call between event records on the stream, [average kernel ms per launch of the call])."""
+        evs_ = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+        for i, e in enumerate(evs_):
+            e[0].record(stream)
+            if call(i) != 0:
+                raise RuntimeError("a lotts call failed")
+            e[1].record(stream)
+        torch.cuda.synchronize()
+        nl = ctypes.c_int32()
+        buf = (ctypes.c_float * (reps * launches_per_call))()
+        assert lib.lotts_timer_start(reps * launches_per_call) == 0
+        for i in range(reps):
+            call(i)
+        assert lib.lotts_timer_stop(ctypes.byref(nl), buf) == 0 and nl.value == reps * launches_per_call
+        kern = [sum(buf[j::launches_per_call]) / reps for j in range(launches_per_call)]
+        return sum(e[0].elapsed_time(e[1]) for e in evs_) / reps, kern
+
     # ---- the widenings, outside the timed region: acceptance straight from bf16 logits (reads every
     # logit row once instead of reading logits, writing p and q and reading them back), and the
     # confidence-weighted aggregation
@@ -291,29 +309,19 @@ def main() -> int:
                                       P(d0["accept_len"]), P(d0["next_token"]), None, P(ws_lg), ws_lg_bytes, sh)
     for i in range(8):
         assert lg_call(i) == 0
-    evl = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(100)]
-    for i, e in enumerate(evl):
-        e[0].record(stream)
-        lg_call(i)
-        e[1].record(stream)
-    torch.cuda.synchronize()
-    lg_ms = sum(e[0].elapsed_time(e[1]) for e in evl) / len(evl)
+    lg_ms, lg_kern = time_op(lg_call, 100, 4)
     lg_bytes = cfg.B * (2 * cfg.k + 1) * cfg.V * 2
-    out["spec_accept_logits"] = {"ms": lg_ms, "algorithmic_bytes": lg_bytes, "logit_dtype": "bf16",
+    out["spec_accept_logits"] = {"ms": lg_ms, "kernel_ms": dict(zip(("lg_max", "lg_sum", "lg_scan", "lg_pick"), lg_kern)),
+                                 "algorithmic_bytes": lg_bytes, "logit_dtype": "bf16",
                                  "GB/s": lg_bytes / (lg_ms * 1e-3) / 1e9,
                                  "frac_of_hbm_peak": lg_bytes / (lg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     Tc = 1024
     conf = 0.3 + 0.7 * torch.rand((1, cfg.B, Tc), generator=gen, device=dev)
     cw = torch.empty((1,), dtype=torch.int32, device=dev)
     cs = torch.empty((1,), dtype=torch.float32, device=dev)
-    evc = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(50)]
-    for e in evc:
-        e[0].record(stream)
-        lib.confidence_vote(1, cfg.B, Tc, P(d0["answers"]), P(conf), None, 1, 1, P(cw), P(cs), sh)
-        e[1].record(stream)
-    torch.cuda.synchronize()
-    out["confidence_vote"] = {"ms": sum(e[0].elapsed_time(e[1]) for e in evc) / len(evc), "scores_per_branch": Tc,
-                              "mode": "avg-vote"}
+    cv_ms, cv_kern = time_op(lambda i: lib.confidence_vote(1, cfg.B, Tc, P(d0["answers"]), P(conf), None, 1, 1, P(cw),
+                                                           P(cs), sh), 50, 1)
+    out["confidence_vote"] = {"ms": cv_ms, "kernel_ms": cv_kern[0], "scores_per_branch": Tc, "mode": "avg-vote"}
 
     # weight GEMMs of one 32B-shaped decoder layer for the step's M = B * (k + 1) tokens (hidden 5120,
     # 40/8 heads of 128, MLP 27648): QKV, O, gate+up, down.  Weight copies are rotated like the KV sets.
@@ -330,15 +338,13 @@ def main() -> int:
         call = lambda i: lib.skinny_gemm(Mg, Ng, Kg, P(Xg), Kg, P(Ws[i % ncopies]), Kg, P(Yg), Ng, P(wsg), wsb, sh)
         for i in range(6):
             assert call(i) == 0
-        evg = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(40)]
-        for i, e in enumerate(evg):
-            e[0].record(stream)
-            call(i)
-            e[1].record(stream)
-        torch.cuda.synchronize()
-        ms = sum(e[0].elapsed_time(e[1]) for e in evg) / len(evg)
+        assert lib.lotts_timer_start(4) == 0
+        call(0)
+        nl = ctypes.c_int32()
+        assert lib.lotts_timer_stop(ctypes.byref(nl), None) == 0   # 2 launches when K is split
+        ms, kern = time_op(call, 40, nl.value)
         nbytes = 2 * (Ng * Kg + Mg * Kg + Mg * Ng)
-        gemms[name_] = {"M": Mg, "N": Ng, "K": Kg, "ms": ms, "algorithmic_bytes": nbytes,
+        gemms[name_] = {"M": Mg, "N": Ng, "K": Kg, "ms": ms, "kernel_ms": kern, "algorithmic_bytes": nbytes,
                         "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "TFLOP/s": 2.0 * Mg * Ng * Kg / (ms * 1e-3) / 1e12}
         del Ws, Xg, Yg, wsg

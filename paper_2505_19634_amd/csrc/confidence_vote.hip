@@ -39,10 +39,21 @@ __global__ __launch_bounds__(kConfThreads) void confidence_vote_kernel(int B, in
         unsigned long long sum = 0, mn = ~0ull;
         if (in && ans >= 0) {
             const float* c = conf + ((size_t)n * B + b) * T;
-            for (int t = sub; t < len; t += LPB) {
-                const unsigned long long q = __float2ull_rz(c[t] * 1073741824.0f);  // trunc(c * 2^30)
-                sum += q;
-                mn = q < mn ? q : mn;
+            // 16 independent loads at a time: one load per iteration would cost a memory latency each
+            for (int t0 = sub; t0 < len; t0 += 16 * LPB) {
+                float v[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int t = t0 + e * LPB;
+                    v[e] = c[t < len ? t : len - 1];
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const unsigned long long q = __float2ull_rz(v[e] * 1073741824.0f);  // trunc(c * 2^30)
+                    const bool use = t0 + e * LPB < len;
+                    sum += use ? q : 0ull;
+                    mn = (use && q < mn) ? q : mn;
+                }
             }
         }
         for (int d = LPB >> 1; d >= 1; d >>= 1) {  // xor shuffles stay inside the aligned group of LPB lanes

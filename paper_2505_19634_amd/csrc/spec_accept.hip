@@ -121,13 +121,24 @@ __global__ __launch_bounds__(kAccThreads) void accept_scan_kernel(int B, int k, 
     const int hi = (lo + chunk < V) ? lo + chunk : V;
     unsigned long long s_res = 0, s_p = 0;
     if (VEC) {
-        for (int i = lo + tid * 4; i < hi; i += kAccThreads * 4) {
-            const float4 pv = *reinterpret_cast<const float4*>(prow + i);
-            float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (has_q) qv = *reinterpret_cast<const float4*>(qrow + i);
-            s_p += fixed_weight(pv.x) + fixed_weight(pv.y) + fixed_weight(pv.z) + fixed_weight(pv.w);
-            s_res += fixed_weight(residual(pv.x, qv.x)) + fixed_weight(residual(pv.y, qv.y)) +
-                     fixed_weight(residual(pv.z, qv.z)) + fixed_weight(residual(pv.w, qv.w));
+        // two groups of 4 per row in flight: all four loads are issued before the first is used
+        for (int i = lo + tid * 4; i < hi; i += kAccThreads * 8) {
+            const int i2 = i + kAccThreads * 4;
+            const bool in2 = i2 < hi;
+            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 pv[2] = {*reinterpret_cast<const float4*>(prow + i), zero};
+            float4 qv[2] = {zero, zero};
+            if (in2) pv[1] = *reinterpret_cast<const float4*>(prow + i2);
+            if (has_q) {
+                qv[0] = *reinterpret_cast<const float4*>(qrow + i);
+                if (in2) qv[1] = *reinterpret_cast<const float4*>(qrow + i2);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {  // zeros weigh nothing
+                s_p += fixed_weight(pv[e].x) + fixed_weight(pv[e].y) + fixed_weight(pv[e].z) + fixed_weight(pv[e].w);
+                s_res += fixed_weight(residual(pv[e].x, qv[e].x)) + fixed_weight(residual(pv[e].y, qv[e].y)) +
+                         fixed_weight(residual(pv[e].z, qv[e].z)) + fixed_weight(residual(pv[e].w, qv[e].w));
+            }
         }
     } else {
         for (int i = lo + tid; i < hi; i += kAccThreads) {
