@@ -158,12 +158,12 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # ---- the timed region: exactly K steps, sync on both sides.  The library's kernel timer picks out the
-    # verify_attention call of every 4th step: its launch carries its own HIP event pair on the launch
+    # verify_attention call of every 8th step: its launch carries its own HIP event pair on the launch
     # stream, which reads the kernel's start and end on the device (the dominant kernel's launch
     # duration, without the gaps that event records around a call would add).  A timed launch costs the
     # queue about 7 us more than a plain one, hence not every step.
     K = args.steps
-    EVERY = 4
+    EVERY = 8
     n_launch = ctypes.c_int32()
     assert lib.lotts_timer_start(8) == 0
     lib.verify_attention(*calls[0][0])
@@ -259,7 +259,7 @@ def main() -> int:
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
                      "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms, "launches_timed": n_timed,
-                     "timing": "HIP event pair attached to the dispatch, every 4th step of the timed region",
+                     "timing": "HIP event pair attached to the dispatch, every %dth step of the timed region" % EVERY,
                      "avg_merge_launch_ms": merge_ms,
                      "avg_call_ms_event_records_around_call": attn_ms_bracket,
                      "avg_call_ms_single_set_cache_resident": attn_ms_resident,
