@@ -1,6 +1,7 @@
 // majority_vote: the answer most branches give (paper Section 1 / Section 4.1: branches are
 // aggregated by majority voting).  One workgroup per question; B is tens to a few thousand
-// ids, so this is a latency-bound O(B^2 / 256) count in LDS.
+// ids, so this is a latency-bound O(B^2 / 256) count in LDS -- or, for up to 64 branches, in the
+// lanes of a single wavefront.
 #include "lotts_common.h"
 
 namespace lotts {
@@ -54,14 +55,49 @@ __global__ __launch_bounds__(kVoteThreads) void majority_vote_kernel(int B, cons
     }
 }
 
+// Up to 64 answers (the paper's branch counts): one wavefront, one answer per lane, no LDS and no
+// barrier -- the whole kernel is one load, B shuffles and one store.
+__global__ __launch_bounds__(kWave) void majority_vote_wave_kernel(int B, const int32_t* __restrict__ answers,
+                                                                   int32_t* __restrict__ winner,
+                                                                   int32_t* __restrict__ winner_count) {
+    const int n = blockIdx.x, lane = threadIdx.x;
+    const int32_t ai = lane < B ? answers[(size_t)n * B + lane] : -1;
+    int votes = 0;
+    bool first = true;
+    for (int j = 0; j < B; ++j) {
+        const int32_t aj = __shfl(ai, j, kWave);
+        const bool same = (aj == ai);
+        votes += same;
+        first = first && !(same && j < lane);
+    }
+    unsigned long long key = 0;  // same key as the general kernel
+    if (ai >= 0 && first) key = ((unsigned long long)votes << 32) | (0xFFFFFFFFu - (unsigned)lane);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned long long o = shfl_down_u64(key, d);
+        key = o > key ? o : key;
+    }
+    key = shfl_u64(key, 0);
+    const int wl = (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFu));
+    const int32_t wa = __shfl(ai, key ? wl : 0, kWave);
+    if (lane == 0) {
+        winner[n] = key ? wa : -1;
+        winner_count[n] = (int32_t)(key >> 32);
+    }
+}
+
 }  // namespace lotts
 
 extern "C" int majority_vote(int32_t N, int32_t B, const int32_t* answers, int32_t* winner, int32_t* winner_count,
                              void* stream) {
     if (!answers || !winner || !winner_count) return LOTTS_ERR_NULL;
     if (N < 1 || B < 1 || B > lotts::kVoteMaxB) return LOTTS_ERR_SHAPE;
-    LOTTS_LAUNCH(lotts::majority_vote_kernel, dim3(N), dim3(lotts::kVoteThreads), (hipStream_t)stream, B,
-                       answers, winner, winner_count);
+    if (B <= lotts::kWave)
+        LOTTS_LAUNCH(lotts::majority_vote_wave_kernel, dim3(N), dim3(lotts::kWave), (hipStream_t)stream, B, answers,
+                     winner, winner_count);
+    else
+        LOTTS_LAUNCH(lotts::majority_vote_kernel, dim3(N), dim3(lotts::kVoteThreads), (hipStream_t)stream, B, answers,
+                     winner, winner_count);
     return lotts::check_launch();
 }
 

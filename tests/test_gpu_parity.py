@@ -225,7 +225,7 @@ def test_accept_is_deterministic(lotts):
 
 
 # ---------------------------------------------------------------------------- vote
-@pytest.mark.parametrize("N,B", [(1, 16), (1, 1), (7, 64), (3, 4096), (50, 33)])
+@pytest.mark.parametrize("N,B", [(1, 16), (1, 1), (7, 64), (5, 65), (4, 63), (3, 4096), (50, 33)])
 def test_vote(lotts, oracle, N, B):
     cfg = S.CONFIGS["C3"].with_(B=B)
     a = S.vote_inputs(cfg, N=N, salt=B)
