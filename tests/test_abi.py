@@ -89,6 +89,54 @@ def test_calls_are_rejected_before_any_launch(lib):
     assert lib.majority_vote(1, 5000, one, one, one, None) == -2
 
 
+def test_widenings_are_rejected_before_any_launch(lib):
+    """Error paths of the later entry points; nothing here reaches a launch."""
+    one = ctypes.c_void_p(4096)
+    f1 = ctypes.c_float(1.0)
+    big = 1 << 30
+    lg = lambda B, k, V, zt, zd, dt, it, dr, u, n, t, ws, wsb: lib.spec_accept_logits(B, k, V, zt, zd, dt, it, dr, u, n, t,
+                                                                                   None, ws, wsb, None)
+    assert lib.spec_accept_logits_workspace_bytes(16, 3, 152064) > 0
+    assert lib.spec_accept_logits_workspace_bytes(16, 3, (1 << 20) + 1) == 0
+    assert lib.spec_accept_logits_workspace_bytes(16, 257, 100) == 0
+    assert lg(4, 2, 100, None, one, 1, f1, one, one, one, one, one, big) == -1
+    assert lg(4, 2, 100, one, None, 1, f1, one, one, one, one, one, big) == -1
+    assert lg(4, 2, 100, one, one, 1, f1, None, one, one, one, one, big) == -1
+    assert lg(4, 0, 100, one, None, 1, f1, None, one, one, one, one, 8) == -4           # k = 0 needs no draft side: the workspace check is reached
+    assert lg(4, 2, 100, one, one, 7, f1, one, one, one, one, one, big) == -3
+    assert lg(4, 2, 100, one, one, 1, ctypes.c_float(0.0), one, one, one, one, one, big) == -2
+    assert lg(4, 2, 100, one, one, 1, ctypes.c_float(float("nan")), one, one, one, one, one, big) == -2
+    assert lg(4, 2, 100, one, one, 1, f1, one, one, one, one, one, 8) == -4
+    assert lg(4, 2, 100, one, one, 1, f1, one, one, one, one, ctypes.c_void_p(4096 + 4), big) == -2
+    assert lg(0, 2, 100, one, one, 1, f1, one, one, one, one, one, big) == -2
+    cv = lib.confidence_vote
+    assert cv(1, 16, 8, None, one, None, 1, 1, one, one, None) == -1
+    assert cv(1, 16, 8, one, one, None, 2, 1, one, one, None) == -2
+    assert cv(1, 16, 8, one, one, None, 1, -1, one, one, None) == -2
+    assert cv(1, 2000, 8, one, one, None, 1, 1, one, one, None) == -2
+    assert cv(1, 16, 0, one, one, None, 1, 1, one, one, None) == -2
+    assert lib.skinny_gemm_workspace_bytes(64, 5120, 5120) > 0
+    assert lib.skinny_gemm_workspace_bytes(129, 5120, 5120) == 0
+    assert lib.skinny_gemm_workspace_bytes(64, 5124, 5120) == 0
+    assert lib.skinny_gemm_workspace_bytes(64, 5120, 5100) == 0
+    gm = lib.skinny_gemm
+    assert gm(64, 512, 512, None, 512, one, 512, one, 512, one, big, None) == -1
+    assert gm(64, 512, 512, one, 512, one, 512, one, 512, None, big, None) == -1
+    assert gm(64, 512, 512, one, 500, one, 512, one, 512, one, big, None) == -2          # row pitch shorter than K
+    assert gm(64, 512, 512, one, 512, one, 516, one, 512, one, big, None) == -2          # pitch not a multiple of 8
+    assert gm(64, 512, 512, ctypes.c_void_p(4096 + 8), 512, one, 512, one, 512, one, big, None) == -2
+    assert gm(64, 512, 512, one, 512, one, 512, one, 512, one, 16, None) == -4
+    assert gm(0, 512, 512, one, 512, one, 512, one, 512, one, big, None) == -2
+
+
+def test_kernel_timer_host_side(lib):
+    n = ctypes.c_int32(-1)
+    assert lib.lotts_timer_start(0) == -2 and lib.lotts_timer_start((1 << 20) + 1) == -2
+    assert lib.lotts_timer_stop(None, None) == -1
+    assert lib.lotts_timer_stop(ctypes.byref(n), None) == 0 and n.value == 0          # never started: nothing timed
+    assert lib.lotts_timer_pause(1) == 0 and lib.lotts_timer_pause(0) == 0
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     import paper_2505_19634_amd as lotts
