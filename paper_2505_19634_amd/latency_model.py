@@ -1,0 +1,187 @@
+"""Latency-aware configuration search on measured kernel times (paper Section 3.3, Algorithm 1).
+
+The paper picks the number of branches B and the draft length gamma that maximise accuracy under a
+latency budget T.  Its accuracy side needs the paper's models and datasets; its latency side is what
+this library computes.  This module measures the latency side on the GPU -- the device time of the
+kernels of one verify step of a decoder of a given shape, taken with the library's kernel timer --
+and runs the library's greedy_search over it with a SYNTHETIC accuracy surface (stated below), so the
+search is exercised end to end on real MI355X latencies.  Nothing here is one of the paper's
+experiments.
+
+Verify step of the target model for B branches and gamma drafts (M = B * (gamma + 1) new tokens):
+per layer QKV projection, attention, O projection, gate+up and down projections (skinny_gemm and
+verify_attention, one layer's buffers timed and multiplied by the layer count), then the LM head and
+the acceptance from logits.  Norms, rotary embedding, activation and KV append are not modelled (they
+are outside this library); the draft model's gamma sequential steps cost `draft_ratio` times a
+one-token step of the target each (an assumption: a draft model a tenth of the target's size).
+
+    python -m paper_2505_19634_amd.latency_model --shape 3B --budget-s 4
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import binding
+
+
+@dataclass(frozen=True)
+class ModelShape:
+    name: str
+    layers: int
+    hidden: int
+    Hq: int
+    Hkv: int
+    D: int
+    mlp: int
+    V: int
+
+
+SHAPES = {
+    "3B": ModelShape("3B-shaped decoder", 36, 2048, 16, 2, 128, 11008, 151936),
+    "32B": ModelShape("32B-shaped decoder", 64, 5120, 40, 8, 128, 27648, 152064),
+}
+
+
+class StepTimer:
+    """Holds one layer's worth of synthetic weights and caches for a shape and times verify steps on them."""
+
+    def __init__(self, shape: ModelShape, prefix: int, max_private: int, max_B: int, max_gamma: int, device="cuda:0"):
+        self.s, self.P, self.Lmax, self.dev = shape, prefix, max_private, torch.device(device)
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(7)
+        bf = lambda *sh: (torch.randn(*sh, generator=g, device=self.dev) * 0.5).to(torch.bfloat16)
+        w = lambda n, k: (torch.randn(n, k, generator=g, device=self.dev) * k ** -0.5).to(torch.bfloat16)
+        s = shape
+        self.W = {"qkv": w((s.Hq + 2 * s.Hkv) * s.D, s.hidden), "o": w(s.hidden, s.Hq * s.D),
+                  "gate_up": w(2 * s.mlp, s.hidden), "down": w(s.hidden, s.mlp), "lm_head": w(s.V, s.hidden)}
+        self.Kpre, self.Vpre = bf(s.Hkv, prefix, s.D), bf(s.Hkv, prefix, s.D)
+        self.Kpriv, self.Vpriv = bf(max_B, s.Hkv, max_private, s.D), bf(max_B, s.Hkv, max_private, s.D)
+        self.max_B, self.max_gamma = max_B, max_gamma
+        self._cache = {}
+
+    def _gemm_ms(self, M: int, W: torch.Tensor) -> float:
+        """Kernel time of Y = X W^T for M tokens (pieces of at most 128 tokens, the library's limit)."""
+        total = 0.0
+        for m0 in range(0, M, 128):
+            m = min(128, M - m0)
+            X = torch.zeros((m, W.shape[1]), dtype=torch.bfloat16, device=self.dev)
+            total += self._timed(lambda: binding.skinny_gemm(X, W))
+        return total
+
+    @staticmethod
+    def _timed(call, reps: int = 3) -> float:
+        """Smallest of `reps` sums of the kernel times of one call (after one untimed call)."""
+        call()
+        best = float("inf")
+        for _ in range(reps):
+            with binding.kernel_timer(8) as t:
+                call()
+            best = min(best, sum(t.ms))
+        return best
+
+    def verify_step_ms(self, B: int, gamma: int, private: int) -> dict:
+        """Device milliseconds of the kernels of one verify step: {"layer": per layer, "head": LM head + acceptance,
+        "total": layers * layer + head}.  `private` = private tokens per branch before the step."""
+        key = (B, gamma, private)
+        if key in self._cache:
+            return self._cache[key]
+        s, R = self.s, gamma + 1
+        assert 1 <= B <= self.max_B and 0 <= gamma <= self.max_gamma and private + R <= self.Lmax
+        M = B * R
+        layer = sum(self._gemm_ms(M, self.W[n]) for n in ("qkv", "o", "gate_up", "down"))
+        Q = torch.zeros((B, R, s.Hq, s.D), dtype=torch.bfloat16, device=self.dev)
+        pl = torch.full((B,), private + R, dtype=torch.int32, device=self.dev)
+        args = (Q, self.Kpre, self.Vpre, self.Kpriv[:B], self.Vpriv[:B], pl)
+        layer += self._timed(lambda: binding.verify_attention(*args))
+        head = self._gemm_ms(M, self.W["lm_head"])
+        zt = torch.zeros((B, R, s.V), dtype=torch.bfloat16, device=self.dev)
+        zd = torch.zeros((B, gamma, s.V), dtype=torch.bfloat16, device=self.dev) if gamma else None
+        dr = torch.zeros((B, gamma), dtype=torch.int32, device=self.dev) if gamma else None
+        u = torch.full((B, R), 0.5, dtype=torch.float32, device=self.dev)
+        head += self._timed(lambda: binding.spec_accept_logits(zt, zd, dr, u))
+        out = {"layer": layer, "head": head, "total": s.layers * layer + head}
+        self._cache[key] = out
+        return out
+
+
+def expected_tokens_per_step(alpha: float, gamma: int) -> float:
+    """Tokens a branch emits per verify step when each draft is accepted with probability alpha:
+    1 + alpha + ... + alpha^gamma (the accepted drafts plus the resampled or bonus token)."""
+    return float(gamma + 1) if alpha >= 1.0 else (1.0 - alpha ** (gamma + 1)) / (1.0 - alpha)
+
+
+def synthetic_accuracy(B: int, tokens: float, *, p_inf: float = 0.62, half_tokens: float = 2500.0,
+                       wrong_classes: int = 12, trials: int = 4000, seed: int = 11) -> float:
+    """A stand-in for the paper's accuracy measurements, NOT data: a branch that may generate `tokens` tokens answers
+    correctly with probability p = p_inf * (1 - 2^(-tokens / half_tokens)); wrong answers spread evenly over
+    `wrong_classes` ids; the question counts as solved when the correct id wins the plurality vote, a tie for the
+    first place counting as one share among the tied ids.  Seeded Monte Carlo, so the surface is a fixed function
+    of (B, tokens)."""
+    p = p_inf * (1.0 - 2.0 ** (-tokens / half_tokens))
+    g = np.random.default_rng(seed)
+    right = g.random((trials, B)) < p
+    wrong_id = g.integers(0, wrong_classes, (trials, B))
+    n_right = right.sum(1)
+    wrong_counts = np.zeros((trials, wrong_classes), dtype=np.int64)
+    for c in range(wrong_classes):
+        wrong_counts[:, c] = ((wrong_id == c) & ~right).sum(1)
+    top = wrong_counts.max(1)
+    tied = (wrong_counts == top[:, None]).sum(1)
+    credit = np.where(n_right > top, 1.0, np.where((n_right == top) & (n_right > 0), 1.0 / (1.0 + tied), 0.0))
+    return float(credit.mean())
+
+
+def search(shape, budget_s: float, *, prefix: int = 512, context: int = 4096, alpha: float = 0.8,
+           draft_ratio: float = 0.1, B_max: int = 64, gamma_max: int = 7, verbose: bool = False) -> dict:
+    """Greedy (B, gamma) search under the latency budget on measured step times.  Returns the chosen configuration,
+    the table of evaluated points and the search's own counters."""
+    shape = SHAPES[shape] if isinstance(shape, str) else shape
+    timer = StepTimer(shape, prefix, context, B_max, gamma_max)
+    evaluated = {}
+
+    def tts_task(B: int, gamma: int, T: float) -> float:
+        # mid-generation cache length: half the context is a fair average over a generation
+        private = max(gamma + 1, context // 2) - (gamma + 1)
+        verify = timer.verify_step_ms(B, gamma, private)["total"]
+        draft = gamma * draft_ratio * timer.verify_step_ms(B, 0, private)["total"]
+        step_ms = verify + draft
+        per_token_ms = step_ms / expected_tokens_per_step(alpha, gamma)
+        tokens = min(float(context - prefix), T * 1e3 / per_token_ms)
+        acc = synthetic_accuracy(B, tokens)
+        evaluated[(B, gamma)] = {"step_ms": step_ms, "ms_per_token": per_token_ms, "tokens_in_budget": tokens, "accuracy": acc}
+        if verbose:
+            print("  B=%-3d gamma=%d  step %.3f ms  %.3f ms/token  %6.0f tokens in %.0f s  accuracy %.3f" % (
+                B, gamma, step_ms, per_token_ms, tokens, T, acc), flush=True)
+        return acc
+
+    B, gamma, acc, rounds, evals = binding.greedy_search(tts_task, budget_s, B_max, gamma_max)
+    return {"shape": shape.name, "budget_s": budget_s, "B": B, "gamma": gamma, "accuracy": acc, "rounds": rounds,
+            "evaluations": evals, "grid_evaluations": (int(math.log2(B_max)) + 1) * (gamma_max + 1),
+            "evaluated": {"B%d_g%d" % k: v for k, v in evaluated.items()},
+            "assumptions": {"alpha": alpha, "draft_ratio": draft_ratio, "prefix": prefix, "context": context,
+                            "accuracy": "synthetic surface, see synthetic_accuracy"}}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--shape", choices=sorted(SHAPES), default="3B")
+    ap.add_argument("--budget-s", type=float, default=4.0)
+    ap.add_argument("--alpha", type=float, default=0.8)
+    ap.add_argument("--draft-ratio", type=float, default=0.1)
+    ap.add_argument("--B-max", type=int, default=64)
+    ap.add_argument("--gamma-max", type=int, default=7)
+    a = ap.parse_args()
+    out = search(a.shape, a.budget_s, alpha=a.alpha, draft_ratio=a.draft_ratio, B_max=a.B_max, gamma_max=a.gamma_max,
+                 verbose=True)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())

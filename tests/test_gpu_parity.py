@@ -477,3 +477,22 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed(lotts, oracle):
         torch.cuda.synchronize()
         assert torch.equal(O, want[0]) and torch.equal(n, want[1]) and torch.equal(t, want[2]), rep
         assert torch.equal(w_g, w_eager) and torch.equal(c_g, c_eager)
+
+
+# ---------------------------------------------------------------------------- search on measured latencies
+def test_greedy_search_on_measured_step_latencies(lotts):
+    """Algorithm 1 driven by kernel times measured on this GPU (tiny decoder shape) and a synthetic accuracy surface:
+    the latency side is real, the bookkeeping of the search must hold, and every evaluated point carries a measured
+    step time."""
+    from paper_2505_19634_amd import latency_model as lm
+    shape = lm.ModelShape("tiny decoder", 2, 512, 8, 2, 64, 1024, 4096)
+    out = lm.search(shape, 0.5, prefix=64, context=512, B_max=8, gamma_max=3)
+    print("greedy on measured latencies:", {k: out[k] for k in ("B", "gamma", "accuracy", "rounds", "evaluations")}, flush=True)
+    assert out["B"] in (1, 2, 4, 8) and 0 <= out["gamma"] <= 3
+    assert out["evaluations"] <= 2 * out["rounds"] + 1 and out["evaluations"] <= out["grid_evaluations"]
+    assert len(out["evaluated"]) == out["evaluations"]
+    assert all(v["step_ms"] > 0.0 and 0.0 <= v["accuracy"] <= 1.0 for v in out["evaluated"].values())
+    assert out["accuracy"] == max(v["accuracy"] for k, v in out["evaluated"].items()
+                                  if k == "B%d_g%d" % (out["B"], out["gamma"]))
+    assert lm.expected_tokens_per_step(0.8, 3) == pytest.approx(1 + 0.8 + 0.64 + 0.512)
+    assert lm.expected_tokens_per_step(1.0, 3) == 4.0 and lm.expected_tokens_per_step(0.5, 0) == 1.0
