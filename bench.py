@@ -325,7 +325,7 @@ def main() -> int:
 
     # weight GEMMs of one 32B-shaped decoder layer for the step's M = B * (k + 1) tokens (hidden 5120,
     # 40/8 heads of 128, MLP 27648): QKV, O, gate+up, down.  Weight copies are rotated like the KV sets.
-    Mg = min(cfg.B * cfg.R, 128)
+    Mg = min(cfg.B * cfg.R, 256)
     gemms = {}
     for name_, (Ng, Kg) in {"qkv_proj": (7168, 5120), "o_proj": (5120, 5120), "gate_up_proj": (55296, 5120),
                             "down_proj": (5120, 27648)}.items():

@@ -197,7 +197,7 @@ size_t skinny_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
  * weights for the 32B model).
  *   Y[m][n] = sum_k X[m][k] * W[n][k]
  *   X [M][K] bf16 (row pitch ldx elements), W [N][K] bf16 (ldw), Y [M][N] bf16 out (ldy)
- *   1 <= M <= 128; N a multiple of 8; K a multiple of 128; ldx, ldw multiples of 8, ldy of 4;
+ *   1 <= M <= 256; N a multiple of 8; K a multiple of 128; ldx, ldw multiples of 8, ldy of 4;
  *   X, W, workspace 16-byte aligned, Y 8-byte aligned
  * bf16 products accumulate in fp32 on the matrix cores; W is read from HBM once.  When N is
  * small the K range is split over workgroups and the fp32 partials are summed in a fixed order

@@ -320,7 +320,7 @@ def greedy_search(tts_task, T: float, B_max: int = 64, gamma_max: int = 7):
 
 def skinny_gemm(X: torch.Tensor, W: torch.Tensor, *, out: Optional[torch.Tensor] = None,
                 workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    """Y = X @ W.T for bf16 X [M][K] (M <= 128) and W [N][K] on the GPU; rows may be strided."""
+    """Y = X @ W.T for bf16 X [M][K] (M <= 256) and W [N][K] on the GPU; rows may be strided."""
     lib = load()
     if not X.is_cuda or X.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
         raise TypeError("skinny_gemm takes bfloat16 tensors on the GPU")

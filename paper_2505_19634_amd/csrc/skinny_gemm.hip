@@ -1,14 +1,16 @@
-// skinny_gemm: Y[M][N] = X[M][K] W[N][K]^T for the B * (k + 1) new tokens of a verify forward (M of a few
-// tens) against one weight matrix (paper Section 3.1: the step is bound by loading the weights; Appendix:
+// skinny_gemm: Y[M][N] = X[M][K] W[N][K]^T for the B * (k + 1) new tokens of a verify forward (M up to
+// 256) against one weight matrix (paper Section 3.1: the step is bound by loading the weights; Appendix:
 // 64 GB of weights for the 32B model).  bf16 in, fp32 accumulate on the matrix cores, bf16 out.
 // HBM-bound on streaming W once: 2 * M flop per weight byte is far below the MFMA balance.
 //
-//   skinny_gemm_kernel<MT>  grid (blocks of 128 weight rows, K splits).  Each of the 4 wavefronts owns 32
+//   skinny_gemm_kernel<MT>  up to 64 tokens; grid (blocks of 128 weight rows, K splits).  Each of the 4 wavefronts owns 32
 //       weight rows and walks the K range in chunks of 128: the W tile (32 x 128, 8 KB) comes in with
 //       coalesced non-temporal 16-byte loads two chunks ahead, is staged through a wavefront-private LDS
-//       slab and read back as the MFMA A operand; the X chunk (up to 128 x 128) is fetched once per
+//       slab and read back as the MFMA A operand; the X chunk (up to 256 x 128) is fetched once per
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
+//   skinny_gemm_wide_kernel<MT>  more than 64 tokens; grid (blocks of 256 weight rows, K splits): 64 weight
+//       rows per wavefront, so that every X fragment read from LDS feeds two MFMAs.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -26,8 +28,10 @@ constexpr int kGemmRows = 32;                         // weight rows per wavefro
 constexpr int kGemmBlockN = kGemmWaves * kGemmRows;   // weight rows per workgroup
 constexpr int kGemmChunk = 128;                       // K elements per chunk
 constexpr int kGemmRowBytes = kGemmChunk * 2 + 16;    // LDS row pitch: conflict-free 16-byte row reads
-constexpr int kGemmMaxM = 128;
+constexpr int kGemmMaxM = 256;
 constexpr int kGemmMaxSplit = 32;
+constexpr int kGemmWideRows = 64;                     // weight rows per wavefront of the wide kernel
+constexpr int kGemmWideBlockN = kGemmWaves * kGemmWideRows;
 
 struct GemmParams {
     const __bf16 *X, *W;
@@ -38,26 +42,44 @@ struct GemmParams {
 };
 
 struct GemmPlan {
-    int mt, nblocks, ksplit;
+    int mt, wide, nblocks, ksplit;
 };
+// K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
+// Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
+// worst choice (a few units run two workgroups and everybody waits for them), so the count stays at
+// or below one per unit -- or, when two fit a unit and every workgroup still gets a long run of
+// chunks, at or below two per unit.
+static inline int plan_ksplit(int nblocks, int chunks, bool two_per_cu) {
+    if (nblocks >= kNumCU) return 1;
+    int ks = two_per_cu ? (2 * kNumCU) / nblocks : kNumCU / nblocks;
+    if (two_per_cu && chunks / ks < 16) ks = kNumCU / nblocks;
+    const int max_ks = chunks / 4 > 0 ? chunks / 4 : 1;  // at least 4 chunks per workgroup
+    if (ks > max_ks) ks = max_ks;
+    if (ks > kGemmMaxSplit) ks = kGemmMaxSplit;
+    return ks < 1 ? 1 : ks;
+}
+
 static inline GemmPlan plan_gemm(int M, int N, int K) {
     GemmPlan pl;
     pl.mt = (M + 31) / 32;
-    pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
     const int chunks = K / kGemmChunk;
-    // Few weight rows: split K so that the launch fills the chip.  Measured on the 32B-shaped layers:
-    // a workgroup count just above the number of compute units is the worst choice (a few units run
-    // two workgroups and everybody waits for them), so the count stays at or below one per unit --
-    // or, when every workgroup still gets a long run of chunks, at or below two per unit.
-    int ks = 1;
-    if (pl.nblocks < kNumCU) {
-        ks = (2 * kNumCU) / pl.nblocks;
-        if (chunks / ks < 16) ks = kNumCU / pl.nblocks;
-        const int max_ks = chunks / 4 > 0 ? chunks / 4 : 1;  // at least 4 chunks per workgroup
-        if (ks > max_ks) ks = max_ks;
-        if (ks > kGemmMaxSplit) ks = kGemmMaxSplit;
+    // The wide kernel (64 weight rows per wavefront, 256 per workgroup, one workgroup per unit) reuses
+    // every X fragment twice and halves the X traffic.  More than 64 tokens need it: with 32 rows per
+    // wavefront the LDS fragment reads bound the kernel.  Up to 64 tokens it wins when its workgroups
+    // still get long runs of chunks (gate+up, down), and loses on short ones (QKV, O).
+    const int nb_wide = (N + kGemmWideBlockN - 1) / kGemmWideBlockN;
+    const int ks_wide = plan_ksplit(nb_wide, chunks, false);
+    pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
+#ifdef LOTTS_TUNING
+    if (const char* e = getenv("LOTTS_GEMM_WIDE")) pl.wide = atoi(e);
+#endif
+    if (pl.wide) {
+        pl.nblocks = nb_wide;
+        pl.ksplit = ks_wide;
+    } else {
+        pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
+        pl.ksplit = plan_ksplit(pl.nblocks, chunks, true);
     }
-    pl.ksplit = ks < 1 ? 1 : ks;
 #ifdef LOTTS_TUNING
     if (const char* e = getenv("LOTTS_GEMM_KSPLIT")) pl.ksplit = atoi(e);
 #endif
@@ -65,7 +87,7 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
 }
 
 template <int MT>
-__global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_kernel(const GemmParams p) {
+__global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const GemmParams p) {
     constexpr int XROWS = 32 * MT;
     __shared__ __attribute__((aligned(16))) unsigned char xbuf[2][XROWS * kGemmRowBytes];
     __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][kGemmRows * kGemmRowBytes];
@@ -126,16 +148,24 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
             fetch_x(c + 2, xst);
             fetch_w(c + 2, w);
         }
-        // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k)
+        // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k); the fragments of
+        // step s + 1 are requested before the MFMAs of step s (see the wide kernel)
+        auto frags = [&](int s, g_bf16x8& a, g_bf16x8 (&b)[MT]) {
+            a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                b[t] = *reinterpret_cast<const g_bf16x8*>(xb + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
+        };
+        g_bf16x8 fa[2], fb[2][MT];
+        frags(0, fa[0], fb[0]);
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const g_bf16x8 a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
+            if (s + 1 < 8) frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const g_bf16x8 b =
-                    *reinterpret_cast<const g_bf16x8*>(xb + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
-            }
+            for (int t = 0; t < MT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1], fb[s & 1][t], acc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     if (c_lo < c_hi) {
@@ -170,6 +200,126 @@ __global__ __launch_bounds__(kGemmThreads, (MT > 2 ? 1 : 2)) void skinny_gemm_ke
             }
         }
     }
+}
+
+// More than 64 tokens.  Each wavefront owns 64 weight rows (two MFMA row tiles) and all M tokens, so an X
+// fragment read from LDS feeds two MFMAs and the workgroup's X chunk serves 256 weight rows.  One W chunk
+// (64 x 128, 16 KB per wavefront) is in flight while the previous one is multiplied, as in the attention
+// kernel; one X tile in LDS, rewritten behind a barrier once every wavefront has finished with it.
+template <int MT>
+__global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const GemmParams p) {
+    constexpr int XROWS = 32 * MT;
+    constexpr int XPT = XROWS * 16 / kGemmThreads;  // 16-byte pieces of an X chunk per thread
+    __shared__ __attribute__((aligned(16))) unsigned char xbuf[XROWS * kGemmRowBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][kGemmWideRows * kGemmRowBytes];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int ln = lane & 31, hh = lane >> 5;
+    const int n0 = blockIdx.x * kGemmWideBlockN + wave * kGemmWideRows;
+    const int chunks = p.K / kGemmChunk;
+    const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
+    const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
+    unsigned char* wslab = wslab_all[wave];
+
+    const int w_row = lane >> 4, w_ch = lane & 15;  // a load instruction covers 4 whole 256-byte row pieces
+    g_u32x4 wst[16], xst[XPT];
+    auto fetch_w = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            int n = n0 + i * 4 + w_row;
+            n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
+            wst[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
+        }
+    };
+    auto fetch_x = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int idx = tid + i * kGemmThreads;
+            int m = idx >> 4;
+            m = m < p.M ? m : p.M - 1;
+            xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
+        }
+    };
+    g_f32x16 acc[2][MT];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][t][i] = 0.f;
+
+    if (c_lo < c_hi) {
+        fetch_x(c_lo);  // X before W: loads complete in issue order and X is wanted first
+        fetch_w(c_lo);
+    }
+    for (int c = c_lo; c < c_hi; ++c) {
+        __syncthreads();  // every wavefront has multiplied the previous chunk out of the X tile
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int idx = tid + i * kGemmThreads;
+            *reinterpret_cast<g_u32x4*>(xbuf + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
+        }
+        __syncthreads();  // the X chunk is complete
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
+        if (c + 1 < c_hi) {
+            fetch_x(c + 1);
+            fetch_w(c + 1);
+        }
+        // Y^T[n][m] += sum_k W[n][k] X[m][k]: two W fragments per k step, every X fragment feeds two MFMAs.
+        // The fragments of step s + 1 are requested before the MFMAs of step s are issued (the scheduling
+        // barriers keep the compiler from sinking each read down to its use, where it would be waited for
+        // with nothing else in flight: one wavefront per SIMD has no neighbour to hide an LDS latency).
+        auto frags = [&](int s, g_bf16x8 (&a)[2], g_bf16x8 (&b)[MT]) {
+            a[0] = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
+            a[1] = *reinterpret_cast<const g_bf16x8*>(wslab + (32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                b[t] = *reinterpret_cast<const g_bf16x8*>(xbuf + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
+        };
+        constexpr int NF = MT <= 7 ? 2 : 1;  // two fragment sets; one at 256 tokens, where registers run out
+        g_bf16x8 fa[NF][2], fb[NF][MT];
+        if (NF == 2) frags(0, fa[0], fb[0]);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            if (NF == 2) {
+                if (s + 1 < 8) frags(s + 1, fa[(s + 1) & (NF - 1)], fb[(s + 1) & (NF - 1)]);
+            } else {
+                frags(s, fa[0], fb[0]);  // all reads of the step first, then the MFMAs as their operands arrive
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][0], fb[s & (NF - 1)][t], acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][1], fb[s & (NF - 1)][t], acc[1][t], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // register i of this lane: output row m = t * 32 + ln, column n = n0 + r * 32 + (i / 4) * 8 + hh * 4 + i % 4
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int m = t * 32 + ln;
+            if (m >= p.M) continue;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int n = n0 + r * 32 + q4 * 8 + hh * 4;
+                if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
+                if (p.ksplit == 1) {
+                    g_bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[r][t][q4 * 4 + e];
+                    *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
+                } else {
+                    *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) =
+                        make_float4(acc[r][t][q4 * 4 + 0], acc[r][t][q4 * 4 + 1], acc[r][t][q4 * 4 + 2],
+                                    acc[r][t][q4 * 4 + 3]);
+                }
+            }
+        }
 }
 
 __global__ __launch_bounds__(256) void skinny_gemm_reduce_kernel(const GemmParams p) {
@@ -225,11 +375,21 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
     hipStream_t s = (hipStream_t)stream;
     const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads);
-    switch (pl.mt) {
-        case 1: LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p); break;
-        case 2: LOTTS_LAUNCH(skinny_gemm_kernel<2>, grid, block, s, p); break;
-        case 3: LOTTS_LAUNCH(skinny_gemm_kernel<3>, grid, block, s, p); break;
-        default: LOTTS_LAUNCH(skinny_gemm_kernel<4>, grid, block, s, p); break;
+    if (pl.wide) {
+        switch (pl.mt) {
+            case 1: LOTTS_LAUNCH(skinny_gemm_wide_kernel<1>, grid, block, s, p); break;
+            case 2: LOTTS_LAUNCH(skinny_gemm_wide_kernel<2>, grid, block, s, p); break;
+            case 3: LOTTS_LAUNCH(skinny_gemm_wide_kernel<3>, grid, block, s, p); break;
+            case 4: LOTTS_LAUNCH(skinny_gemm_wide_kernel<4>, grid, block, s, p); break;
+            case 5: LOTTS_LAUNCH(skinny_gemm_wide_kernel<5>, grid, block, s, p); break;
+            case 6: LOTTS_LAUNCH(skinny_gemm_wide_kernel<6>, grid, block, s, p); break;
+            case 7: LOTTS_LAUNCH(skinny_gemm_wide_kernel<7>, grid, block, s, p); break;
+            default: LOTTS_LAUNCH(skinny_gemm_wide_kernel<8>, grid, block, s, p); break;
+        }
+    } else if (pl.mt == 1) {
+        LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);
+    } else {
+        LOTTS_LAUNCH(skinny_gemm_kernel<2>, grid, block, s, p);
     }
     int rc = check_launch();
     if (rc != LOTTS_OK || pl.ksplit == 1) return rc;

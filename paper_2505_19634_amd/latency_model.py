@@ -66,10 +66,10 @@ class StepTimer:
         self._cache = {}
 
     def _gemm_ms(self, M: int, W: torch.Tensor) -> float:
-        """Kernel time of Y = X W^T for M tokens (pieces of at most 128 tokens, the library's limit)."""
+        """Kernel time of Y = X W^T for M tokens (pieces of at most 256 tokens, the library's limit)."""
         total = 0.0
-        for m0 in range(0, M, 128):
-            m = min(128, M - m0)
+        for m0 in range(0, M, 256):
+            m = min(256, M - m0)
             X = torch.zeros((m, W.shape[1]), dtype=torch.bfloat16, device=self.dev)
             total += self._timed(lambda: binding.skinny_gemm(X, W))
         return total

@@ -116,7 +116,7 @@ def test_widenings_are_rejected_before_any_launch(lib):
     assert cv(1, 2000, 8, one, one, None, 1, 1, one, one, None) == -2
     assert cv(1, 16, 0, one, one, None, 1, 1, one, one, None) == -2
     assert lib.skinny_gemm_workspace_bytes(64, 5120, 5120) > 0
-    assert lib.skinny_gemm_workspace_bytes(129, 5120, 5120) == 0
+    assert lib.skinny_gemm_workspace_bytes(257, 5120, 5120) == 0
     assert lib.skinny_gemm_workspace_bytes(64, 5124, 5120) == 0
     assert lib.skinny_gemm_workspace_bytes(64, 5120, 5100) == 0
     gm = lib.skinny_gemm

@@ -361,6 +361,8 @@ def test_confidence_vote(lotts, oracle, N, B, T):
 # ---------------------------------------------------------------------------- weight GEMM of the verify forward
 @pytest.mark.parametrize("M,N,K", [
     (64, 512, 1024), (40, 136, 256), (5, 8, 128), (1, 1000, 384), (128, 256, 512), (97, 264, 640),
+    (129, 520, 384), (192, 2048, 2048), (256, 640, 1280), (231, 136, 128),   # more than 128 tokens: one X tile, two barriers
+    (192, 11008, 2048),     # 3B-shaped MLP up projection for B = 64 branches, k = 2
     (64, 7168, 5120),       # 32B-shaped QKV projection for B * (k + 1) = 64 tokens (K split over workgroups)
     (64, 5120, 27648),      # 32B-shaped MLP down projection
     (36, 27648, 5120),      # 32B-shaped MLP up projection, M of the long-draft config

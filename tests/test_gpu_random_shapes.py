@@ -99,7 +99,7 @@ def test_accept_logits_random_shape(lotts, oracle, seed):
 @pytest.mark.parametrize("seed", range(12))
 def test_skinny_gemm_random_shape(lotts, oracle, seed):
     g = np.random.default_rng(4000 + seed)
-    M = int(g.integers(1, 129))
+    M = int(g.integers(1, 257))
     N = 8 * int(g.integers(1, 400))
     K = 128 * int(g.integers(1, 40))
     print("random gemm case", seed, M, N, K, flush=True)
