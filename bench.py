@@ -60,8 +60,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (branches shard trivially, "
-              "see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by branch with no "
+              "exchange inside attention or acceptance: N GPUs would run N independent copies of these kernels)"
+              % args.gpus, file=sys.stderr)
         return 2
 
     import numpy as np
