@@ -367,6 +367,21 @@ def main() -> int:
                                "kind": "oracle",
                                "sample": "%d full steps of the same workload (input set 0), fp64, OpenMP over "
                                          "(branch, head)" % reps}
+        # the same on one thread (a shorter sample: about 5 s)
+        all_threads = oracle.n_threads()
+        oracle.set_threads(1)
+        reps1, t1cpu = 0, 0.0
+        while t1cpu < 5.0 and reps1 < 10:
+            c0 = time.perf_counter()
+            oracle.verify_attention(a0["Q"], a0["Kpre"], a0["Vpre"], a0["Kpriv"], a0["Vpriv"], a0["priv_len"],
+                                    want_lse=False)
+            oracle.spec_accept(s0["p"], s0["q"], s0["draft"], s0["u"])
+            oracle.majority_vote(answers0)
+            t1cpu += time.perf_counter() - c0
+            reps1 += 1
+        oracle.set_threads(all_threads)
+        out["cpu_baseline"]["value_one_thread"] = tokens * reps1 / t1cpu
+        out["cpu_baseline"]["sample_one_thread"] = "%d full steps" % reps1
     print(json.dumps(out))
     return 0
 
