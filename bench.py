@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", help="C2, C3, C5 or C4xB (e.g. C4x16)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--torch-sdpa", action="store_true",
+                    help="also time torch's scaled_dot_product_attention on the same attention problem (context only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by branch with no "
@@ -350,6 +352,29 @@ def main() -> int:
                         "TFLOP/s": 2.0 * Mg * Ng * Kg / (ms * 1e-3) / 1e12}
         del Ws, Xg, Yg, wsg
     out["skinny_gemm"] = gemms
+
+    # ---- context only, on request: the attention problem handed to torch's scaled_dot_product_attention.  It has no
+    # shared-prefix form and no bottom-right causal mode, so the prefix is replicated per branch and the mask is explicit.
+    if args.torch_sdpa and bf:
+        import torch.nn.functional as F
+        Sx = cfg.P + cfg.L
+        tq = [d["Q"].permute(0, 2, 1, 3).contiguous() for d in sets]
+        tk = [torch.cat([d["Kpre"][None].expand(cfg.B, -1, -1, -1), d["Kpriv"]], dim=2).contiguous() for d in sets]
+        tv = [torch.cat([d["Vpre"][None].expand(cfg.B, -1, -1, -1), d["Vpriv"]], dim=2).contiguous() for d in sets]
+        mask = torch.ones(cfg.R, Sx, dtype=torch.bool, device=dev).tril(diagonal=Sx - cfg.R)
+        sdpa = lambda i: F.scaled_dot_product_attention(tq[i % nsets], tk[i % nsets], tv[i % nsets], attn_mask=mask,
+                                                        enable_gqa=True)
+        for i in range(4):
+            sdpa(i)
+        eb2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        eb2[0].record(stream)
+        for i in range(20):
+            sdpa(i)
+        eb2[1].record(stream)
+        torch.cuda.synchronize()
+        out["torch_sdpa_context"] = {"ms_back_to_back": eb2[0].elapsed_time(eb2[1]) / 20,
+                                     "note": "prefix replicated per branch, boolean mask, enable_gqa; torch " + torch.__version__}
+        del tq, tk, tv
 
     # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
     if not args.no_cpu_baseline:
