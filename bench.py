@@ -59,7 +59,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--torch-sdpa", action="store_true",
-                    help="also time torch's scaled_dot_product_attention on the same attention problem (context only)")
+                    help="also time torch on the same problems: scaled_dot_product_attention and linear (context only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by branch with no "
@@ -375,6 +375,23 @@ def main() -> int:
         out["torch_sdpa_context"] = {"ms_back_to_back": eb2[0].elapsed_time(eb2[1]) / 20,
                                      "note": "prefix replicated per branch, boolean mask, enable_gqa; torch " + torch.__version__}
         del tq, tk, tv
+        # the four weight GEMMs through torch.nn.functional.linear (the vendor GEMM library), same shapes and M
+        lin = {}
+        for name_, (Ng, Kg) in {"qkv_proj": (7168, 5120), "o_proj": (5120, 5120), "gate_up_proj": (55296, 5120),
+                                "down_proj": (5120, 27648)}.items():
+            Ws = [(torch.randn((Ng, Kg), generator=gen, device=dev) * Kg ** -0.5).to(torch.bfloat16) for _ in range(3)]
+            Xg = torch.randn((Mg, Kg), generator=gen, device=dev).to(torch.bfloat16)
+            for i in range(4):
+                F.linear(Xg, Ws[i % 3])
+            el = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            el[0].record(stream)
+            for i in range(20):
+                F.linear(Xg, Ws[i % 3])
+            el[1].record(stream)
+            torch.cuda.synchronize()
+            lin[name_] = el[0].elapsed_time(el[1]) / 20
+            del Ws, Xg
+        out["torch_linear_context"] = {"M": Mg, "ms_back_to_back": lin}
 
     # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
     if not args.no_cpu_baseline:
