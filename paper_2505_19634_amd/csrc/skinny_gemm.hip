@@ -9,8 +9,8 @@
 //       slab and read back as the MFMA A operand; the X chunk (up to 256 x 128) is fetched once per
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
-//   skinny_gemm_wide_kernel<MT>  more than 64 tokens; grid (blocks of 256 weight rows, K splits): 64 weight
-//       rows per wavefront, so that every X fragment read from LDS feeds two MFMAs.
+//   skinny_gemm_wide_kernel<MT, RT>  more than 64 tokens, or long K runs; grid (blocks of 128 * RT weight rows,
+//       K splits): RT row tiles per wavefront; with RT = 2 every X fragment read from LDS feeds two MFMAs.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -30,8 +30,6 @@ constexpr int kGemmChunk = 128;                       // K elements per chunk
 constexpr int kGemmRowBytes = kGemmChunk * 2 + 16;    // LDS row pitch: conflict-free 16-byte row reads
 constexpr int kGemmMaxM = 256;
 constexpr int kGemmMaxSplit = 32;
-constexpr int kGemmWideRows = 64;                     // weight rows per wavefront of the wide kernel
-constexpr int kGemmWideBlockN = kGemmWaves * kGemmWideRows;
 
 struct GemmParams {
     const __bf16 *X, *W;
@@ -42,7 +40,7 @@ struct GemmParams {
 };
 
 struct GemmPlan {
-    int mt, wide, nblocks, ksplit;
+    int mt, wide, rt, nblocks, ksplit;
 };
 // K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
 // Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
@@ -63,12 +61,15 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     GemmPlan pl;
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
-    // The wide kernel (64 weight rows per wavefront, 256 per workgroup, one workgroup per unit) reuses
-    // every X fragment twice and halves the X traffic.  More than 64 tokens need it: with 32 rows per
-    // wavefront the LDS fragment reads bound the kernel.  Up to 64 tokens it wins when its workgroups
-    // still get long runs of chunks (gate+up, down), and loses on short ones (QKV, O).
-    const int nb_wide = (N + kGemmWideBlockN - 1) / kGemmWideBlockN;
-    const int ks_wide = plan_ksplit(nb_wide, chunks, false);
+    // The wide kernel with two row tiles per wavefront (64 weight rows, 256 per workgroup, one workgroup
+    // per unit) reuses every X fragment twice and halves the X traffic.  Up to 64 tokens it wins when its
+    // workgroups still get long runs of chunks (gate+up, down), and loses on short ones (QKV, O).  For
+    // 65..128 tokens the same loop with one row tile per wavefront fits two workgroups per unit (two
+    // wavefronts per SIMD hide each other's barrier and load waits) and measured 10 % faster; beyond 128
+    // tokens the accumulators leave room for one wavefront per SIMD only and the two-tile form is back.
+    pl.rt = (pl.mt == 3 || pl.mt == 4) ? 1 : 2;
+    const int nb_wide = (N + kGemmBlockN * pl.rt - 1) / (kGemmBlockN * pl.rt);
+    const int ks_wide = plan_ksplit(nb_wide, chunks, pl.rt == 1);
     pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
 #ifdef LOTTS_TUNING
     if (const char* e = getenv("LOTTS_GEMM_WIDE")) pl.wide = atoi(e);
@@ -202,29 +203,31 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
     }
 }
 
-// More than 64 tokens.  Each wavefront owns 64 weight rows (two MFMA row tiles) and all M tokens, so an X
-// fragment read from LDS feeds two MFMAs and the workgroup's X chunk serves 256 weight rows.  One W chunk
-// (64 x 128, 16 KB per wavefront) is in flight while the previous one is multiplied, as in the attention
-// kernel; one X tile in LDS, rewritten behind a barrier once every wavefront has finished with it.
-template <int MT>
-__global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const GemmParams p) {
+// More than 64 tokens, and long K runs at any M.  Each wavefront owns RT MFMA row tiles of weight rows
+// (32 * RT) and all M tokens; with RT = 2 an X fragment read from LDS feeds two MFMAs and the workgroup's
+// X chunk serves 256 weight rows.  One W chunk (8 KB * RT per wavefront) is in flight while the previous
+// one is multiplied, as in the attention kernel; one X tile in LDS, rewritten behind a barrier once every
+// wavefront has finished with it.
+template <int MT, int RT>
+__global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_wide_kernel(const GemmParams p) {
+    constexpr int WROWS = 32 * RT;
     constexpr int XROWS = 32 * MT;
     constexpr int XPT = XROWS * 16 / kGemmThreads;  // 16-byte pieces of an X chunk per thread
     __shared__ __attribute__((aligned(16))) unsigned char xbuf[XROWS * kGemmRowBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][kGemmWideRows * kGemmRowBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][WROWS * kGemmRowBytes];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31, hh = lane >> 5;
-    const int n0 = blockIdx.x * kGemmWideBlockN + wave * kGemmWideRows;
+    const int n0 = blockIdx.x * (kGemmWaves * WROWS) + wave * WROWS;
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
     unsigned char* wslab = wslab_all[wave];
 
     const int w_row = lane >> 4, w_ch = lane & 15;  // a load instruction covers 4 whole 256-byte row pieces
-    g_u32x4 wst[16], xst[XPT];
+    g_u32x4 wst[8 * RT], xst[XPT];
     auto fetch_w = [&](int c) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 8 * RT; ++i) {
             int n = n0 + i * 4 + w_row;
             n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
             wst[i] = __builtin_nontemporal_load(
@@ -240,9 +243,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const
             xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
         }
     };
-    g_f32x16 acc[2][MT];
+    g_f32x16 acc[RT][MT];
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const
         }
         __syncthreads();  // the X chunk is complete
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
+        for (int i = 0; i < 8 * RT; ++i)
             *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
         if (c + 1 < c_hi) {
             fetch_x(c + 1);
@@ -271,15 +274,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const
         // The fragments of step s + 1 are requested before the MFMAs of step s are issued (the scheduling
         // barriers keep the compiler from sinking each read down to its use, where it would be waited for
         // with nothing else in flight: one wavefront per SIMD has no neighbour to hide an LDS latency).
-        auto frags = [&](int s, g_bf16x8 (&a)[2], g_bf16x8 (&b)[MT]) {
-            a[0] = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
-            a[1] = *reinterpret_cast<const g_bf16x8*>(wslab + (32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
+        auto frags = [&](int s, g_bf16x8 (&a)[RT], g_bf16x8 (&b)[MT]) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+                a[r] = *reinterpret_cast<const g_bf16x8*>(wslab + (r * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
 #pragma unroll
             for (int t = 0; t < MT; ++t)
                 b[t] = *reinterpret_cast<const g_bf16x8*>(xbuf + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
         };
         constexpr int NF = MT <= 7 ? 2 : 1;  // two fragment sets; one at 256 tokens, where registers run out
-        g_bf16x8 fa[NF][2], fb[NF][MT];
+        g_bf16x8 fa[NF][RT], fb[NF][MT];
         if (NF == 2) frags(0, fa[0], fb[0]);
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -291,15 +295,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void skinny_gemm_wide_kernel(const
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][0], fb[s & (NF - 1)][t], acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][1], fb[s & (NF - 1)][t], acc[1][t], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+                    acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][r], fb[s & (NF - 1)][t], acc[r][t], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
     // register i of this lane: output row m = t * 32 + ln, column n = n0 + r * 32 + (i / 4) * 8 + hh * 4 + i % 4
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < RT; ++r)
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const int m = t * 32 + ln;
@@ -377,14 +382,14 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads);
     if (pl.wide) {
         switch (pl.mt) {
-            case 1: LOTTS_LAUNCH(skinny_gemm_wide_kernel<1>, grid, block, s, p); break;
-            case 2: LOTTS_LAUNCH(skinny_gemm_wide_kernel<2>, grid, block, s, p); break;
-            case 3: LOTTS_LAUNCH(skinny_gemm_wide_kernel<3>, grid, block, s, p); break;
-            case 4: LOTTS_LAUNCH(skinny_gemm_wide_kernel<4>, grid, block, s, p); break;
-            case 5: LOTTS_LAUNCH(skinny_gemm_wide_kernel<5>, grid, block, s, p); break;
-            case 6: LOTTS_LAUNCH(skinny_gemm_wide_kernel<6>, grid, block, s, p); break;
-            case 7: LOTTS_LAUNCH(skinny_gemm_wide_kernel<7>, grid, block, s, p); break;
-            default: LOTTS_LAUNCH(skinny_gemm_wide_kernel<8>, grid, block, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 2>), grid, block, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 2>), grid, block, s, p); break;
+            case 3: LOTTS_LAUNCH((skinny_gemm_wide_kernel<3, 1>), grid, block, s, p); break;
+            case 4: LOTTS_LAUNCH((skinny_gemm_wide_kernel<4, 1>), grid, block, s, p); break;
+            case 5: LOTTS_LAUNCH((skinny_gemm_wide_kernel<5, 2>), grid, block, s, p); break;
+            case 6: LOTTS_LAUNCH((skinny_gemm_wide_kernel<6, 2>), grid, block, s, p); break;
+            case 7: LOTTS_LAUNCH((skinny_gemm_wide_kernel<7, 2>), grid, block, s, p); break;
+            default: LOTTS_LAUNCH((skinny_gemm_wide_kernel<8, 2>), grid, block, s, p); break;
         }
     } else if (pl.mt == 1) {
         LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);
