@@ -498,3 +498,26 @@ def test_greedy_search_on_measured_step_latencies(lotts):
                                   if k == "B%d_g%d" % (out["B"], out["gamma"]))
     assert lm.expected_tokens_per_step(0.8, 3) == pytest.approx(1 + 0.8 + 0.64 + 0.512)
     assert lm.expected_tokens_per_step(1.0, 3) == 4.0 and lm.expected_tokens_per_step(0.5, 0) == 1.0
+
+
+def test_attention_strided_q_and_o(lotts, oracle):
+    """Q and O handed over as views into larger tensors (extra heads and extra positions around them): only the
+    strides change, the padding is never touched."""
+    cfg = BF.with_(B=3, P=96, L=200)
+    a = S.attention_inputs(cfg)
+    d = attn_to_dev(cfg, a)
+    big_q = torch.zeros((cfg.B, cfg.R + 2, cfg.Hq + 3, cfg.D), dtype=torch.bfloat16, device=DEV)
+    q_view = big_q[:, 1:1 + cfg.R, 2:2 + cfg.Hq]
+    q_view.copy_(d["Q"])
+    big_o = torch.full((cfg.B, cfg.R + 1, cfg.Hq + 5, cfg.D), 7.0, dtype=torch.bfloat16, device=DEV)
+    o_view = big_o[:, :cfg.R, 4:4 + cfg.Hq]
+    assert not q_view.is_contiguous() and not o_view.is_contiguous()
+    lotts.verify_attention(q_view, d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"], out=o_view)
+    O2 = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    assert torch.equal(o_view, O2)
+    untouched = big_o.clone()
+    untouched[:, :cfg.R, 4:4 + cfg.Hq] = 7.0
+    assert bool((untouched == 7.0).all())                 # nothing outside the view was written
+    Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
+    e_abs, e_fro, _ = attn_errors(o_view, Oref)
+    assert e_abs <= 2e-2 and e_fro <= 1e-2
