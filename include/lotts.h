@@ -87,6 +87,8 @@ size_t verify_attention_workspace_bytes(const lotts_attn_desc *desc);
  *   O      [B][R][Hq][D] dtype, out
  *   lse    [B][R][Hq] fp32, out, may be NULL: natural-log sum of exp of the scaled scores
  *   workspace: >= verify_attention_workspace_bytes(desc), 16-byte aligned, zero-filled before first use
+ *            (see above: arrival counters).  Calls that may overlap in time -- different streams --
+ *            need workspaces of their own; calls on one stream can share one.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs are
  * computed in fp32 throughout.
  */

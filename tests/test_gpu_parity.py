@@ -521,3 +521,25 @@ def test_attention_strided_q_and_o(lotts, oracle):
     Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], a["priv_len"])
     e_abs, e_fro, _ = attn_errors(o_view, Oref)
     assert e_abs <= 2e-2 and e_fro <= 1e-2
+
+
+def test_attention_on_two_streams_with_separate_workspaces(lotts):
+    """Calls that overlap in time need workspaces of their own (the arrival counters live there); given that, two
+    streams can run verify_attention side by side and get exactly the results of running alone."""
+    cfg = BF.with_(B=16, P=128, L=1500)
+    d1 = attn_to_dev(cfg, S.attention_inputs(cfg, salt=1))
+    d2 = attn_to_dev(cfg, S.attention_inputs(cfg, salt=2))
+    call = lambda d, **kw: lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"], **kw)
+    ref1, ref2 = call(d1).clone(), call(d2).clone()
+    torch.cuda.synchronize()
+    ws1 = torch.zeros(16 << 20, dtype=torch.uint8, device=DEV)
+    ws2 = torch.zeros(16 << 20, dtype=torch.uint8, device=DEV)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    o1 = [torch.empty_like(d1["Q"]) for _ in range(6)]
+    o2 = [torch.empty_like(d2["Q"]) for _ in range(6)]
+    for i in range(6):
+        call(d1, out=o1[i], workspace=ws1, stream=s1)
+        call(d2, out=o2[i], workspace=ws2, stream=s2)
+    torch.cuda.synchronize()
+    assert all(torch.equal(o, ref1) for o in o1) and all(torch.equal(o, ref2) for o in o2)
+    assert int(ws1[:65536].view(torch.int32).abs().sum()) == 0 and int(ws2[:65536].view(torch.int32).abs().sum()) == 0
