@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kLgThreads) void lg_max_kernel(int B, int k, int V,
                                                             float* __restrict__ pmax,
                                                             unsigned long long* __restrict__ rsum) {
     __shared__ float sh_m[kLgWaves];
-    const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
+    const int r = blockIdx.x / npieces, pc = blockIdx.x - r * npieces, tid = threadIdx.x;
     const int nt = B * (k + 1);
     const void* z = r < nt ? zt : zd;
     const size_t base = (size_t)(r < nt ? r : r - nt) * V;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kLgThreads) void lg_sum_kernel(int B, int k, int V,
                                                             float* __restrict__ rmax,
                                                             unsigned long long* __restrict__ rsum) {
     __shared__ unsigned long long sh_s[kLgWaves];
-    const int r = blockIdx.y, pc = blockIdx.x, tid = threadIdx.x;
+    const int r = blockIdx.x / npieces, pc = blockIdx.x - r * npieces, tid = threadIdx.x;
     const int nt = B * (k + 1);
     const void* z = r < nt ? zt : zd;
     const size_t base = (size_t)(r < nt ? r : r - nt) * V;
@@ -414,11 +414,15 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
         w1 = p1;
         Z = block_sum_u128(w0 + w1, sh_w);
     }
+    if (Z == 0) {  // a row without any weight (all logits -inf, or +inf / NaN among them): no token; uniform
+        if (tid == 0) next_token[b] = -1;
+        return;
+    }
     unsigned m24 = (unsigned)(u[(size_t)b * (k + 1) + k] * 16777216.0f);
     m24 = m24 > 16777215u ? 16777215u : m24;  // u must be < 1; keeps T < Z regardless
     const u128 T = ((u128)m24 * Z) >> 24;
     u128 excl = block_excl_scan_u128(w0 + w1, sh_w);
-    if (excl <= T && T < excl + w0 + w1) {  // exactly one thread: T < Z and Z > 0 (the row maximum weighs 2^30)
+    if (excl <= T && T < excl + w0 + w1) {  // exactly one thread: T < Z and Z > 0
         const bool second = !(T < excl + w0);
         sh_chunk = c0 + (second ? 1 : 0);
         sh_base = second ? excl + w0 : excl;
@@ -471,7 +475,10 @@ static inline LgLayout lg_layout(int B, int k, int V) {
     return l;
 }
 static inline bool lg_sizes_ok(int B, int k, int V) {
-    return B >= 1 && B <= 65535 && k >= 0 && k <= kLgMaxK && V >= 1 && V <= (1 << 20);
+    if (!(B >= 1 && B <= 65535 && k >= 0 && k <= kLgMaxK && V >= 1 && V <= (1 << 20))) return false;
+    // one workgroup per (piece of a row, row): the launch must fit one grid dimension
+    const long long pieces = (V + kLgPiece - 1) / kLgPiece;
+    return pieces * B * (2 * k + 1) <= 0x7fffffffLL;
 }
 
 template <bool BF16, bool VEC>
@@ -484,7 +491,7 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
     unsigned long long* rsum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_rsum);
     u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
     unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
-    const dim3 sgrid(l.npieces, B * (2 * k + 1));
+    const dim3 sgrid((unsigned)((long long)l.npieces * B * (2 * k + 1)));  // (piece, row) pairs, row-major
     LOTTS_LAUNCH((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
                  rsum);
     int rc = check_launch();

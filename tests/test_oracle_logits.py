@@ -191,3 +191,28 @@ def test_rollback_keeps_exactly_the_verified_tokens(oracle):
         seen.update(n.tolist())
     assert np.array_equal(cache - start, emitted)
     assert seen == set(range(k + 1))                         # every acceptance length occurred
+
+
+def test_rows_without_any_weight_give_no_token(oracle):
+    """A softmax over logits that are all -inf has no mass: every integer weight is 0.  A draft at such a target
+    row cannot be accepted (its probability is 0), nothing can be sampled there, and the token is -1 -- the same
+    convention as the probability path, which returns -1 for a row of zeros."""
+    V, k = 40, 2
+    g = np.random.default_rng(21)
+    zt = g.normal(0, 2, (3, k + 1, V)).astype(np.float32)
+    zd = zt[:, :k].copy()                                    # identical rows: drafts are accepted wherever they weigh
+    zt[1, 1, :] = -np.inf                                    # branch 1: no mass at position 1
+    zt[2, 2, :] = -np.inf                                    # branch 2: no mass at the bonus position
+    E, S = oracle.logit_weights(zt[1, 1])
+    assert S == 0 and not E.any()
+    draft = np.array([[3, 4], [5, 6], [7, 8]], np.int32)
+    u = np.full((3, k + 1), 0.25, np.float32)
+    n, t = oracle.spec_accept_logits(zt, zd, draft, u)
+    assert list(n) == [2, 1, 2] and t[0] >= 0 and t[1] == -1 and t[2] == -1
+    # the probability path on the corresponding distributions (zeros where there is no mass) agrees
+    p = softmax(zt.astype(np.float64), axis=-1)
+    p[1, 1, :] = 0.0
+    p[2, 2, :] = 0.0
+    q = softmax(zd.astype(np.float64), axis=-1)
+    n2, t2 = oracle.spec_accept(p.astype(np.float32), q.astype(np.float32), draft, u)
+    assert list(n2) == [2, 1, 2] and t2[1] == -1 and t2[2] == -1
