@@ -11,11 +11,15 @@
  *     host before anything is launched; a failed call launches nothing.
  *   - Scratch memory is passed in as `workspace`; the *_workspace_bytes queries say how much.
  *     Calls that share a workspace must be ordered on one stream.  spec_accept takes any
- *     contents.  verify_attention keeps arrival counters in the first 64 KiB of its workspace:
- *     the buffer must be ZERO-FILLED ONCE before its first use (hipMemset or a fill kernel);
- *     every call that completes leaves the counters zero again, whatever its geometry, so the
- *     same buffer serves later calls without clearing.  A buffer that was in use by a call
- *     that did not complete (device reset, failed launch) must be cleared again.
+ *     contents.  verify_attention keeps arrival cells in the first 128 KiB of its workspace:
+ *     the buffer must be ZERO-FILLED ONCE before its first use (hipMemset or a fill kernel).
+ *     After that it serves any number of calls of any geometry without clearing: every cell
+ *     carries the tag of the call that wrote it (tags grow from call to call within the
+ *     process), a call treats whatever an earlier call left there as zero arrivals, and a
+ *     call that completes leaves its cells zero.  So a call that never completed (a failed
+ *     launch, an aborted stream) does not spoil the buffer for the calls after it.  The one
+ *     exception is a captured launch that is replayed later: it keeps the tag it was captured
+ *     with, so clear the buffer before replaying a graph after some call on it was aborted.
  */
 #ifndef LOTTS_H
 #define LOTTS_H
@@ -63,7 +67,9 @@ typedef struct {
     int64_t o_stride_b, o_stride_r, o_stride_h;              /* O  [B][R][Hq][D] */
 } lotts_attn_desc;
 
-/* Bytes of workspace verify_attention needs for this geometry (0 if the descriptor is invalid). */
+/* Bytes of workspace verify_attention needs for this geometry; 0 if the descriptor is invalid or the
+ * partials of this geometry would not fit the 2 GiB that the kernels address with 32-bit offsets
+ * (verify_attention then returns LOTTS_ERR_SHAPE). */
 size_t verify_attention_workspace_bytes(const lotts_attn_desc *desc);
 
 /*
@@ -87,7 +93,7 @@ size_t verify_attention_workspace_bytes(const lotts_attn_desc *desc);
  *   O      [B][R][Hq][D] dtype, out
  *   lse    [B][R][Hq] fp32, out, may be NULL: natural-log sum of exp of the scaled scores
  *   workspace: >= verify_attention_workspace_bytes(desc), 16-byte aligned, zero-filled before first use
- *            (see above: arrival counters).  Calls that may overlap in time -- different streams --
+ *            (see above: arrival cells).  Calls that may overlap in time -- different streams --
  *            need workspaces of their own; calls on one stream can share one.
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32 inputs are
  * computed in fp32 throughout.
@@ -143,9 +149,10 @@ size_t spec_accept_logits_workspace_bytes(int32_t B, int32_t k, int32_t V);
  * if all k drafts are accepted, with weights Ep_k(v).  token = first v with
  * W_0 + ... + W_v > floor(trunc(u[b][k] * 2^24) * sum(W) / 2^24).  All in 128-bit integers.
  *
- *   1 <= B <= 65535, 0 <= k <= 256, 1 <= V <= 2^20
+ *   1 <= B <= 65535, 0 <= k <= 256, 1 <= V <= 2^20, ceil(V / 16384) * B * (2k + 1) < 2^31
  *   target_logits [B][k+1][V], draft_logits [B][k][V] (NULL iff k == 0): logit_dtype = LOTTS_F32 or
- *       LOTTS_BF16, finite or -inf; inv_temperature > 0
+ *       LOTTS_BF16, finite or -inf; inv_temperature > 0.  A sampled row without any weight (every
+ *       logit -inf) yields next_token = -1, as in spec_accept.
  *   draft [B][k] int32 (NULL iff k == 0), u [B][k+1] fp32 in [0, 1)
  *   accept_len [B], next_token [B] int32 out
  *   priv_len [B] int32 in/out, NULL to skip: the private length verify_attention was given for

@@ -103,16 +103,22 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
-_workspaces: Dict[Tuple[str, int], torch.Tensor] = {}
+_workspaces: Dict[Tuple[str, int, int], torch.Tensor] = {}
+_retired = []   # grown-out workspaces: kept alive, a kernel enqueued earlier may still be using them
 
 
-def _workspace(kind: str, device: torch.device, nbytes: int) -> torch.Tensor:
-    """One cached scratch tensor per entry point and device, grown on demand.  Allocated zero-filled:
-    verify_attention wants its arrival counters zero at first use and leaves them zero."""
-    key = (kind, device.index if device.index is not None else torch.cuda.current_device())
+def _workspace(kind: str, device: torch.device, nbytes: int, stream: Optional[torch.cuda.Stream]) -> torch.Tensor:
+    """One cached scratch tensor per entry point, device and stream, grown on demand.  Calls on different streams
+    may overlap in time, so they never share one.  The tensor is allocated and zero-filled on the stream that will
+    use it (verify_attention wants its arrival cells zero at first use), so the fill is ordered before the kernel."""
+    s = torch.cuda.current_stream(device) if stream is None else stream
+    key = (kind, device.index if device.index is not None else torch.cuda.current_device(), int(s.cuda_stream))
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=device)
+        if ws is not None:
+            _retired.append(ws)
+        with torch.cuda.stream(s):
+            ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=device)
         _workspaces[key] = ws
     return ws
 
@@ -167,7 +173,7 @@ def verify_attention(Q: torch.Tensor, Kpre: Optional[torch.Tensor], Vpre: Option
     need = lib.verify_attention_workspace_bytes(ctypes.byref(desc))
     if need == 0:
         raise LottsError(-2, "verify_attention_workspace_bytes")
-    ws = _workspace("attn", Q.device, need) if workspace is None else workspace
+    ws = _workspace("attn", Q.device, need, stream) if workspace is None else workspace
     rc = lib.verify_attention(ctypes.byref(desc), _ptr(Q), _ptr(Kpre), _ptr(Vpre), _ptr(Kpriv), _ptr(Vpriv),
                               _ptr(priv_len), _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
                               _stream_handle(stream))
@@ -204,7 +210,7 @@ def spec_accept(p: torch.Tensor, q: Optional[torch.Tensor], draft: Optional[torc
     need = lib.spec_accept_workspace_bytes(B, k, V)
     if need == 0:
         raise LottsError(-2, "spec_accept_workspace_bytes")
-    ws = _workspace("accept", p.device, need) if workspace is None else workspace
+    ws = _workspace("accept", p.device, need, stream) if workspace is None else workspace
     rc = lib.spec_accept(B, k, V, _ptr(p), _ptr(q), _ptr(draft), _ptr(u), _ptr(accept_len), _ptr(next_token),
                          _ptr(ws), ws.numel() * ws.element_size(), _stream_handle(stream))
     if rc != 0:
@@ -270,7 +276,7 @@ def spec_accept_logits(target_logits: torch.Tensor, draft_logits: Optional[torch
     need = lib.spec_accept_logits_workspace_bytes(B, k, V)
     if need == 0:
         raise LottsError(-2, "spec_accept_logits_workspace_bytes")
-    ws = _workspace("accept_logits", u.device, need) if workspace is None else workspace
+    ws = _workspace("accept_logits", u.device, need, stream) if workspace is None else workspace
     rc = lib.spec_accept_logits(B, k, V, _ptr(target_logits), _ptr(draft_logits), dt, float(inv_temperature), _ptr(draft),
                                 _ptr(u), _ptr(accept_len), _ptr(next_token), _ptr(priv_len), _ptr(ws),
                                 ws.numel() * ws.element_size(), _stream_handle(stream))
@@ -333,7 +339,7 @@ def skinny_gemm(X: torch.Tensor, W: torch.Tensor, *, out: Optional[torch.Tensor]
     need = lib.skinny_gemm_workspace_bytes(M, N, K)
     if need == 0:
         raise LottsError(-2, "skinny_gemm_workspace_bytes")
-    ws = _workspace("gemm", X.device, need) if workspace is None else workspace
+    ws = _workspace("gemm", X.device, need, stream) if workspace is None else workspace
     rc = lib.skinny_gemm(M, N, K, _ptr(X), X.stride(0), _ptr(W), W.stride(0), _ptr(out), out.stride(0), _ptr(ws),
                          ws.numel() * ws.element_size(), _stream_handle(stream))
     if rc != 0:

@@ -71,9 +71,6 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     const int nb_wide = (N + kGemmBlockN * pl.rt - 1) / (kGemmBlockN * pl.rt);
     const int ks_wide = plan_ksplit(nb_wide, chunks, pl.rt == 1);
     pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
-#ifdef LOTTS_TUNING
-    if (const char* e = getenv("LOTTS_GEMM_WIDE")) pl.wide = atoi(e);
-#endif
     if (pl.wide) {
         pl.nblocks = nb_wide;
         pl.ksplit = ks_wide;
@@ -81,9 +78,6 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
         pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
         pl.ksplit = plan_ksplit(pl.nblocks, chunks, true);
     }
-#ifdef LOTTS_TUNING
-    if (const char* e = getenv("LOTTS_GEMM_KSPLIT")) pl.ksplit = atoi(e);
-#endif
     return pl;
 }
 

@@ -33,7 +33,8 @@
 //       spread over the chip instead.
 // fp32 path: attn_f32_kernel, plain fp32 VALU arithmetic, one workgroup per output row; it
 // exists for exactness checks on small fp32 problems, not for speed.
-#include <cstdlib>
+#include <atomic>
+#include <cmath>
 
 #include "lotts_common.h"
 
@@ -71,7 +72,8 @@ struct AttnParams {
     unsigned ws_bytes;
     unsigned off_o, off_ml;    // byte offsets: partial O [Hkv][B*GR][nslots][D] fp32,
                                //               partial (running max in log2 units, sum) [Hkv][B*GR][nslots][2] fp32
-    int* counters;             // [Hkv][B] arrivals, at the start of the workspace; zero between calls
+    unsigned long long* counters;  // [Hkv][B] arrival cells at the start of the workspace: (call tag << 16) | arrivals
+    unsigned long long tag;        // this call's tag, shifted into place: larger than that of any earlier call
     void* O;
     float* lse;
     int B, k, R, Hq, Hkv, G, GR, D, P, Lmax;
@@ -81,9 +83,6 @@ struct AttnParams {
     long long kpriv_stride_b, kpriv_stride_h, kpriv_stride_t;
     long long o_stride_b, o_stride_r, o_stride_h;
     AttnPlan plan;
-#ifdef LOTTS_TUNING
-    long long* dbg;  // development builds: per-workgroup phase timestamps
-#endif
 };
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -107,10 +106,6 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
     pl.nsplit_priv = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
     // A prefix that is short next to the private caches is folded into the private items.
     pl.fold = (d.P > 0 && (long long)d.P * 4 <= d.Lmax) ? 1 : 0;
-#ifdef LOTTS_TUNING  // development builds only: override the plan from the environment
-    if (const char* e = getenv("LOTTS_FOLD")) pl.fold = (d.P > 0) ? atoi(e) : 0;
-    if (const char* e = getenv("LOTTS_NSPLIT_PRIV")) pl.nsplit_priv = atoi(e);
-#endif
     if (d.P > 0 && !pl.fold) {
         const int tiles_pre = ceil_div(d.P, kTile);
         const int tiles_per_item = ceil_div(tiles_priv, pl.nsplit_priv);
@@ -119,9 +114,6 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
         if (cap > kMaxSplit) cap = kMaxSplit;
         if (s > cap) s = cap;
         pl.nsplit_pre = s < 1 ? 1 : s;
-#ifdef LOTTS_TUNING
-        if (const char* e = getenv("LOTTS_NSPLIT_PRE")) pl.nsplit_pre = atoi(e);
-#endif
     } else {
         pl.nsplit_pre = 0;
     }
@@ -130,9 +122,6 @@ static inline AttnPlan plan_attention(const lotts_attn_desc& d) {
     // bandwidth: worth it only while that is a few tens of KB; beyond, a separate launch spreads the
     // merge over the whole chip.
     pl.fused = ((long long)pl.nslots * GR * d.D * 4 <= 48 * 1024) ? 1 : 0;
-#ifdef LOTTS_TUNING
-    if (const char* e = getenv("LOTTS_FUSED")) pl.fused = atoi(e);
-#endif
     pl.n_pre_items = d.Hkv * pl.n_rg_pre * pl.nsplit_pre;
     pl.n_priv_items = d.B * d.Hkv * pl.n_rg_priv * pl.nsplit_priv;
     return pl;
@@ -145,12 +134,20 @@ static inline size_t part_ml_elems(const lotts_attn_desc& d, const AttnPlan& pl)
     return (size_t)d.Hkv * d.B * (d.Hq / d.Hkv) * (d.k + 1) * pl.nslots * 2;
 }
 
-// Workspace: [arrival counters][partial O][partial (max, sum)], each part 256-byte aligned.  The
-// counter block has the same place and size for every geometry, so a buffer whose counters are zero
-// stays usable when the geometry changes: partials of one call never land where another counts.
+// Workspace: [arrival cells][partial O][partial (max, sum)], each part 256-byte aligned.  The
+// cell block has the same place and size for every geometry, so a buffer stays usable when the
+// geometry changes: partials of one call never land where another counts.
+//
+// An arrival cell holds (tag << 16) | arrivals.  Every call draws a tag larger than all earlier ones
+// of this process; an arriving workgroup first raises the cell to (tag, 0) with an atomic maximum,
+// then adds one.  A cell left at zero (a fresh zero-filled buffer, or the reset the last arriver
+// does) and a cell left behind by an earlier call that never completed both start the new call
+// at zero arrivals, so no call can poison the buffer for the next one.
 constexpr int kMaxCounters = 16384;
+constexpr int kTagShift = 16;            // arrivals per cell < 2^16, checked on the host
+static std::atomic<unsigned long long> g_call_tag{0};
 static inline size_t workspace_layout(const lotts_attn_desc& d, const AttnPlan& pl, size_t* off_o, size_t* off_ml) {
-    size_t bytes = (size_t)kMaxCounters * sizeof(int);
+    size_t bytes = (size_t)kMaxCounters * sizeof(unsigned long long);
     if (off_o) *off_o = bytes;
     bytes += part_o_elems(d, pl) * sizeof(float);
     bytes = (bytes + 255) & ~(size_t)255;
@@ -305,14 +302,8 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31;   // MFMA column (query row) / A row (key or d) owned by this lane
     const int hh = lane >> 5;   // which half of each 16-wide k block this lane holds
-#ifdef LOTTS_TUNING
-#define DBG_STAMP(i) do { if (prm.dbg && tid == 0) prm.dbg[(long long)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define DBG_STAMP(i)
-#endif
     const AttnPlan& pl = prm.plan;
     const int GR = prm.GR;
-    DBG_STAMP(0);
 
     // ---- decode the work item: private items first (one per CU starts at once), prefix items after ----
     // Order matters for latency: whatever does not depend on priv_len[b] (the prefix share, the Q
@@ -458,9 +449,7 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
-    DBG_STAMP(1);
     for (int it = 0; it < n_tiles; ++it) {
-        if (it == 1) DBG_STAMP(2);
         const bool folded = it < n_fold;
         const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * run[1].step;
 #pragma unroll
@@ -537,7 +526,6 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         }
     }
 
-    DBG_STAMP(3);
     // ---- combine the 4 wavefronts' states (fixed order) and store the item's partial ----
     // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier all 256
     // threads form sum_w 2^(m_w - m) O_w for the valid rows and write it out, coalesced.
@@ -598,11 +586,12 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     if (!pl.fused) return;  // a separate launch merges (many partials per row: one workgroup would be too slow)
     // ---- arrival: whoever completes the set of partials of a (KV head, branch) merges it ----
     // Every thread waits until its partial stores are acknowledged; then one thread per covered
-    // branch counts the arrival.  Counters start at zero and the last arrival puts the zero back.
-    DBG_STAMP(4);
+    // branch counts the arrival in that branch's cell: raise it to (this call's tag, 0) if it holds
+    // anything older, add one.  The two atomics go to one address from one thread, so they take
+    // effect in program order.  The last arrival puts a zero back, which lets a captured launch
+    // (same tag every time) be replayed.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    DBG_STAMP(5);
     int* sh_last = reinterpret_cast<int*>(sh_l);  // free again; kAttnWaves * kRowTile >= rows of an item
     const int rows_per_item = kRowTile * NQT;
     const int b_first = rho0 / GR, b_last = (rho_end - 1) / GR;
@@ -614,21 +603,17 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             const int rg_lo = (b * GR) / rows_per_item, rg_hi = ((b + 1) * GR - 1) / rows_per_item;
             expected += pl.nsplit_pre * (rg_hi - rg_lo + 1);
         }
-        int* cnt = prm.counters + kvh * prm.B + b;
-        const int last = (atomicAdd(cnt, 1) == expected - 1);
-        if (last) atomicExch(cnt, 0);
+        unsigned long long* cnt = prm.counters + kvh * prm.B + b;
+        atomicMax(cnt, prm.tag);
+        const unsigned long long seen = atomicAdd(cnt, 1ull);
+        const int last = (seen == prm.tag + (unsigned long long)(expected - 1));
+        if (last) atomicExch(cnt, 0ull);
         sh_last[tid] = last;
     }
     __syncthreads();
-#ifdef LOTTS_TUNING
-    if (prm.dbg && tid == 0)  // where the workgroup ran: HW_ID (register 4) and XCC_ID (register 20), read-only
-        prm.dbg[(long long)blockIdx.x * 8 + 6] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |
-                                                 ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);
-#endif
     for (int j = 0; j < nb; ++j)
         if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
     __builtin_amdgcn_s_waitcnt(0);
-    DBG_STAMP(7);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -761,33 +746,22 @@ static int fill_desc(const lotts_attn_desc* in, lotts_attn_desc* d) {
     return LOTTS_OK;
 }
 
-}  // namespace lotts
-
-extern "C" size_t verify_attention_workspace_bytes(const lotts_attn_desc* desc) {
-    using namespace lotts;
-    lotts_attn_desc d;
-    if (fill_desc(desc, &d) != LOTTS_OK) return 0;
+// Bytes of workspace for a checked descriptor; 0 when the geometry cannot be served (partials are
+// addressed with 32-bit byte offsets, arrivals per cell are counted in 16 bits).
+static size_t workspace_need(const lotts_attn_desc& d) {
     if (d.dtype == LOTTS_F32) return 256;  // the fp32 path needs none; keep the pointer non-NULL
     const AttnPlan pl = plan_attention(d);
+    const long long arrivals = (long long)pl.n_rg_priv * pl.nsplit_priv + (long long)pl.nsplit_pre * (pl.n_rg_priv + 1);
+    if (arrivals >= (1 << kTagShift)) return 0;
     const size_t bytes = workspace_layout(d, pl, nullptr, nullptr);
-    return bytes < 0x7fffffffULL ? bytes : 0;  // partials are addressed with 32-bit byte offsets
+    return bytes < 0x7fffffffULL ? bytes : 0;
 }
 
-extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, const void* Kpre, const void* Vpre,
-                                const void* Kpriv, const void* Vpriv, const int32_t* priv_len, void* O, float* lse,
-                                void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace lotts;
-    lotts_attn_desc d;
-    int rc = fill_desc(desc, &d);
-    if (rc != LOTTS_OK) return rc;
-    if (!Q || !Kpriv || !Vpriv || !priv_len || !O || !workspace) return LOTTS_ERR_NULL;
-    if (d.P > 0 && (!Kpre || !Vpre)) return LOTTS_ERR_NULL;
-    if (workspace_bytes < verify_attention_workspace_bytes(desc)) return LOTTS_ERR_WORKSPACE;
-    const uintptr_t align_or = (uintptr_t)Q | (uintptr_t)Kpre | (uintptr_t)Vpre | (uintptr_t)Kpriv | (uintptr_t)Vpriv |
-                               (uintptr_t)O | (uintptr_t)workspace;
-    if (d.dtype == LOTTS_BF16 && (align_or & 15) != 0) return LOTTS_ERR_SHAPE;
-    if ((align_or & 3) != 0) return LOTTS_ERR_SHAPE;
-
+// Everything after the argument checks that both entry points share: plan, parameters, launches.
+// `workspace` holds at least workspace_need(d) bytes.
+static int launch_attention(const lotts_attn_desc& d, const void* Q, const void* Kpre, const void* Vpre,
+                            const void* Kpriv, const void* Vpriv, const int32_t* priv_len, void* O, float* lse,
+                            void* workspace, hipStream_t s) {
     AttnParams prm;
     prm.Q = Q; prm.Kpre = Kpre; prm.Vpre = Vpre; prm.Kpriv = Kpriv; prm.Vpriv = Vpriv;
     prm.priv_len = priv_len;
@@ -800,10 +774,7 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     prm.kpre_stride_h = d.kpre_stride_h; prm.kpre_stride_t = d.kpre_stride_t;
     prm.kpriv_stride_b = d.kpriv_stride_b; prm.kpriv_stride_h = d.kpriv_stride_h; prm.kpriv_stride_t = d.kpriv_stride_t;
     prm.o_stride_b = d.o_stride_b; prm.o_stride_r = d.o_stride_r; prm.o_stride_h = d.o_stride_h;
-#ifdef LOTTS_TUNING
-    prm.dbg = getenv("LOTTS_DBG_PTR") ? (long long*)strtoull(getenv("LOTTS_DBG_PTR"), nullptr, 0) : nullptr;
-#endif
-    hipStream_t s = (hipStream_t)stream;
+    prm.tag = 0;
     const long long rows = (long long)d.B * prm.R * d.Hq;
 
     if (d.dtype == LOTTS_F32) {
@@ -824,7 +795,8 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     prm.ws_bytes = (unsigned)total;
     prm.off_o = (unsigned)off_o;
     prm.off_ml = (unsigned)off_ml;
-    prm.counters = static_cast<int*>(workspace);
+    prm.counters = static_cast<unsigned long long*>(workspace);
+    prm.tag = (g_call_tag.fetch_add(1, std::memory_order_relaxed) + 1) << kTagShift;
     const long long items = (long long)pl.n_pre_items + pl.n_priv_items;
     if (items > 0x7fffffffLL) return LOTTS_ERR_SHAPE;
     const dim3 grid((unsigned)items), block(kAttnThreads);
@@ -833,11 +805,49 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     else if (pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<64, 1>), grid, block, s, prm);
     else LOTTS_LAUNCH((attn_kernel<64, 2>), grid, block, s, prm);
     if (!pl.fused) {
-        rc = check_launch();
+        const int rc = check_launch();
         if (rc != LOTTS_OK) return rc;
         const dim3 mgrid((unsigned)((prm.GR * (d.D / 4) + kAttnThreads - 1) / kAttnThreads), (unsigned)(d.Hkv * d.B));
         if (d.D == 128) LOTTS_LAUNCH(attn_merge_kernel<128>, mgrid, block, s, prm);
         else LOTTS_LAUNCH(attn_merge_kernel<64>, mgrid, block, s, prm);
     }
     return check_launch();
+}
+
+// Pointer checks of both entry points (everything but the workspace).
+static int check_pointers(const lotts_attn_desc& d, const void* Q, const void* Kpre, const void* Vpre, const void* Kpriv,
+                          const void* Vpriv, const int32_t* priv_len, const void* O) {
+    if (!Q || !Kpriv || !Vpriv || !priv_len || !O) return LOTTS_ERR_NULL;
+    if (d.P > 0 && (!Kpre || !Vpre)) return LOTTS_ERR_NULL;
+    const uintptr_t align_or = (uintptr_t)Q | (uintptr_t)Kpre | (uintptr_t)Vpre | (uintptr_t)Kpriv | (uintptr_t)Vpriv |
+                               (uintptr_t)O;
+    if (d.dtype == LOTTS_BF16 && (align_or & 15) != 0) return LOTTS_ERR_SHAPE;
+    if ((align_or & 3) != 0) return LOTTS_ERR_SHAPE;
+    return LOTTS_OK;
+}
+
+}  // namespace lotts
+
+extern "C" size_t verify_attention_workspace_bytes(const lotts_attn_desc* desc) {
+    using namespace lotts;
+    lotts_attn_desc d;
+    if (fill_desc(desc, &d) != LOTTS_OK) return 0;
+    return workspace_need(d);
+}
+
+extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, const void* Kpre, const void* Vpre,
+                                const void* Kpriv, const void* Vpriv, const int32_t* priv_len, void* O, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lotts;
+    lotts_attn_desc d;
+    int rc = fill_desc(desc, &d);
+    if (rc != LOTTS_OK) return rc;
+    rc = check_pointers(d, Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, O);
+    if (rc != LOTTS_OK) return rc;
+    if (!workspace) return LOTTS_ERR_NULL;
+    const size_t need = workspace_need(d);
+    if (need == 0) return LOTTS_ERR_SHAPE;  // a geometry whose partials the 32-bit offsets cannot address
+    if (workspace_bytes < need) return LOTTS_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & (d.dtype == LOTTS_BF16 ? 15 : 3)) != 0) return LOTTS_ERR_SHAPE;
+    return launch_attention(d, Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, O, lse, workspace, (hipStream_t)stream);
 }

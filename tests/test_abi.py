@@ -77,6 +77,10 @@ def test_calls_are_rejected_before_any_launch(lib):
                                 1 << 30, None) == -2
     assert lib.verify_attention(ctypes.byref(make_desc(dtype=5)), one, one, one, one, one, one, one, None, one,
                                 1 << 30, None) == -3
+    # a geometry whose partials would pass 2 GiB: the workspace query answers 0 and the call is refused, not launched
+    huge = make_desc(B=16384, Hkv=1, Hq=64, k=8, P=0, Lmax=4096)
+    assert lib.verify_attention_workspace_bytes(ctypes.byref(huge)) == 0
+    assert lib.verify_attention(ctypes.byref(huge), one, None, None, one, one, one, one, None, one, 1 << 40, None) == -2
     odd = ctypes.c_void_p(4096 + 2)    # bf16 rows must be 16-byte aligned
     assert lib.verify_attention(ctypes.byref(d), odd, one, one, one, one, one, one, None, one, 1 << 30, None) == -2
     assert lib.spec_accept(4, 2, 100, None, one, one, one, one, one, one, 1 << 20, None) == -1
@@ -99,6 +103,8 @@ def test_widenings_are_rejected_before_any_launch(lib):
     assert lib.spec_accept_logits_workspace_bytes(16, 3, 152064) > 0
     assert lib.spec_accept_logits_workspace_bytes(16, 3, (1 << 20) + 1) == 0
     assert lib.spec_accept_logits_workspace_bytes(16, 257, 100) == 0
+    assert lib.spec_accept_logits_workspace_bytes(65535, 256, 1 << 20) == 0       # more (piece, row) pairs than one grid holds
+    assert lg(65535, 256, 1 << 20, one, one, 1, f1, one, one, one, one, one, 1 << 60) == -2
     assert lg(4, 2, 100, None, one, 1, f1, one, one, one, one, one, big) == -1
     assert lg(4, 2, 100, one, None, 1, f1, one, one, one, one, one, big) == -1
     assert lg(4, 2, 100, one, one, 1, f1, None, one, one, one, one, big) == -1
