@@ -102,6 +102,26 @@ int verify_attention(const lotts_attn_desc *desc, const void *Q, const void *Kpr
                      const void *Kpriv, const void *Vpriv, const int32_t *priv_len, void *O, float *lse,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * verify_attention_noalloc -- verify_attention for callers that cannot allocate device memory or
+ * hand over a workspace: code that runs under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same operation, same kernels, same results bit for bit; the arrival
+ * cells and partials live in a 16 MiB scratch array built into the library (static device
+ * memory: each GPU the library runs on holds its copy until the process ends) instead of a
+ * caller's workspace.  The call allocates and frees nothing and calls no allocating routine.
+ *   Limit: geometries with verify_attention_workspace_bytes(desc) > 16 MiB (16777216 bytes) are
+ *   rejected with LOTTS_ERR_WORKSPACE before anything is launched; use verify_attention for those.
+ *   The device that `stream` belongs to must be the calling thread's current device (the scratch
+ *   address is looked up once per device, on the first call made there).
+ *   All calls on one GPU share that GPU's scratch array, so calls that may overlap in time on one
+ *   GPU (different streams, several host threads) race; order them on one stream.  Nothing has to
+ *   be cleared between calls.
+ * Arguments and errors otherwise as for verify_attention.
+ */
+int verify_attention_noalloc(const lotts_attn_desc *desc, const void *Q, const void *Kpre, const void *Vpre,
+                             const void *Kpriv, const void *Vpriv, const int32_t *priv_len, void *O, float *lse,
+                             void *stream);
+
 /* Bytes of workspace spec_accept needs (0 if the sizes are invalid). */
 size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V);
 

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "liblotts.so")
 
 LOTTS_F32, LOTTS_BF16 = 0, 1
 
-EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention",
+EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention", "verify_attention_noalloc",
            "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
            "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "greedy_search",
            "lotts_timer_start", "lotts_timer_pause", "lotts_timer_stop")
@@ -60,6 +60,8 @@ def load() -> ctypes.CDLL:
         lib.verify_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
         lib.verify_attention.restype = ctypes.c_int
         lib.verify_attention.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8 + [vp, sz, vp]
+        lib.verify_attention_noalloc.restype = ctypes.c_int
+        lib.verify_attention_noalloc.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 8 + [vp]
         lib.spec_accept_workspace_bytes.restype = sz
         lib.spec_accept_workspace_bytes.argtypes = [i32, i32, i32]
         lib.spec_accept.restype = ctypes.c_int
@@ -180,6 +182,29 @@ def verify_attention(Q: torch.Tensor, Kpre: Optional[torch.Tensor], Vpre: Option
     if rc != 0:
         raise LottsError(rc, "verify_attention")
     return (out, lse) if return_lse else out
+
+
+def verify_attention_noalloc(Q: torch.Tensor, Kpre: Optional[torch.Tensor], Vpre: Optional[torch.Tensor],
+                             Kpriv: torch.Tensor, Vpriv: torch.Tensor, priv_len: torch.Tensor, out: torch.Tensor, *,
+                             scale: float = 0.0, lse: Optional[torch.Tensor] = None,
+                             stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """verify_attention through the entry point that allocates nothing: the caller brings `out` (and `lse`), the
+    library's built-in scratch replaces the workspace.  Geometries beyond that scratch raise LottsError(-4)."""
+    lib = load()
+    if not Q.is_cuda:
+        raise ValueError("verify_attention_noalloc runs on the GPU only")
+    if Kpre is not None and Kpre.shape[1] == 0:
+        Kpre, Vpre = None, None
+    if Vpriv.stride() != Kpriv.stride() or (Kpre is not None and Vpre.stride() != Kpre.stride()):
+        raise ValueError("K and V of a segment must share strides")
+    if priv_len.dtype != torch.int32:
+        raise TypeError("priv_len must be int32")
+    desc = make_attn_desc(Q, Kpre, Kpriv, out, scale)
+    rc = lib.verify_attention_noalloc(ctypes.byref(desc), _ptr(Q), _ptr(Kpre), _ptr(Vpre), _ptr(Kpriv), _ptr(Vpriv),
+                                      _ptr(priv_len), _ptr(out), _ptr(lse), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "verify_attention_noalloc")
+    return out
 
 
 def spec_accept(p: torch.Tensor, q: Optional[torch.Tensor], draft: Optional[torch.Tensor], u: torch.Tensor, *,

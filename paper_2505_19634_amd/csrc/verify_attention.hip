@@ -826,6 +826,31 @@ static int check_pointers(const lotts_attn_desc& d, const void* Q, const void* K
     return LOTTS_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of the entry point that allocates nothing: arrival cells and partials live in a
+// file-scope device array instead of a caller's workspace.  Each GPU holds its own copy of the array
+// at its own address for the life of the process; in host code the array's name is only a handle, so
+// the address is looked up once per device (with that device current) and the kernels get the
+// looked-up pointer, exactly as they get a workspace pointer.  Zero-initialised when the code object
+// is loaded, which is what the arrival cells want at first use.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LOTTS_ERR_LAUNCH;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {  // first call on this device; two threads racing here look up the same address
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LOTTS_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return LOTTS_OK;
+}
+
 }  // namespace lotts
 
 extern "C" size_t verify_attention_workspace_bytes(const lotts_attn_desc* desc) {
@@ -850,4 +875,22 @@ extern "C" int verify_attention(const lotts_attn_desc* desc, const void* Q, cons
     if (workspace_bytes < need) return LOTTS_ERR_WORKSPACE;
     if (((uintptr_t)workspace & (d.dtype == LOTTS_BF16 ? 15 : 3)) != 0) return LOTTS_ERR_SHAPE;
     return launch_attention(d, Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, O, lse, workspace, (hipStream_t)stream);
+}
+
+extern "C" int verify_attention_noalloc(const lotts_attn_desc* desc, const void* Q, const void* Kpre, const void* Vpre,
+                                        const void* Kpriv, const void* Vpriv, const int32_t* priv_len, void* O,
+                                        float* lse, void* stream) {
+    using namespace lotts;
+    lotts_attn_desc d;
+    int rc = fill_desc(desc, &d);
+    if (rc != LOTTS_OK) return rc;
+    rc = check_pointers(d, Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, O);
+    if (rc != LOTTS_OK) return rc;
+    const size_t need = workspace_need(d);
+    if (need == 0) return LOTTS_ERR_SHAPE;
+    if (need > kScratchBytes) return LOTTS_ERR_WORKSPACE;  // beyond the built-in scratch: use verify_attention
+    void* ptr = nullptr;
+    rc = scratch_of_current_device(&ptr);
+    if (rc != LOTTS_OK) return rc;
+    return launch_attention(d, Q, Kpre, Vpre, Kpriv, Vpriv, priv_len, O, lse, ptr, (hipStream_t)stream);
 }
