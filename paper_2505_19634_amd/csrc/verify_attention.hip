@@ -77,6 +77,7 @@ struct AttnParams {
     void* O;
     float* lse;
     int B, k, R, Hq, Hkv, G, GR, D, P, Lmax;
+    unsigned g_magic;  // ceil(2^32 / G): x / G == umulhi(x, g_magic) for x * G < 2^32
     float scale_log2;  // scale * log2(e)
     long long q_stride_b, q_stride_r, q_stride_h;
     long long kpre_stride_h, kpre_stride_t;
@@ -187,17 +188,19 @@ __device__ __forceinline__ float2 ws_load2(__amdgpu_buffer_rsrc_t r, unsigned by
 
 // ---------------------------------------------------------------------------------------------
 // Merge of the partials of the G*R output rows of one (KV head, branch), run by the workgroup that
-// delivered the last of them:  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// 4 floats per output quad; a thread takes two quads and 8 slots at a time so that 16 sixteen-byte
-// loads are in flight together.  DEV selects device-scope loads (merge inside the attention launch,
-// partials come from the memory side of the L2s) or plain loads (separate merge launch).
+// delivered the last of them:  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s, slots in index
+// order whoever merges.  4 floats per output quad; a thread takes EU quads (256 apart) and CH
+// slots at a time, so that EU * CH sixteen-byte loads are in flight together.  DEV selects
+// device-scope loads (merge inside the attention launch, partials come from the memory side of the
+// L2s) or plain loads (separate merge launch).  With OWN the merging workgroup's own partial (slot
+// own_slot) is taken from its registers -- quad q of thread tid is quad tid + 256 q of the branch
+// -- instead of being read back.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool DEV>
+template <int D, bool DEV, int EU, int CH, bool OWN>
 __device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buffer_rsrc_t rs, int kvh, int b, int tid,
-                                             int e_begin, int e_end) {
+                                             int e_begin, int e_end, int own_slot, const float4 (&own_o)[EU],
+                                             const float2 (&own_ml)[EU]) {
     constexpr int F4 = D / 4;
-    constexpr int CH = 8;  // slots per round of loads
-    constexpr int EU = 2;  // output quads handled together: 2 * 8 sixteen-byte loads in flight per thread
     const int ns = prm.plan.nslots;
     const int n_e = e_end < prm.GR * F4 ? e_end : prm.GR * F4;  // output quads [e_begin, e_end) of this (KV head, branch)
     for (int e0 = e_begin + tid; e0 < n_e; e0 += EU * kAttnThreads) {
@@ -225,13 +228,20 @@ __device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buf
             for (int q = 0; q < EU; ++q)
 #pragma unroll
                 for (int j = 0; j < CH; ++j) {
-                    const bool in = s0 + j < ns;
+                    if (OWN && q * kAttnThreads >= n_e) continue;  // no thread has this quad (uniform)
+                    const bool mine = OWN && s0 + j == own_slot;
+                    const bool in = s0 + j < ns && !mine;
                     mv[q][j] = in ? ws_load2<DEV>(rs, prm.off_ml + (base[q] + s0 + j) * 8u) : make_float2(-INFINITY, 0.f);
                     pv[q][j] = in ? ws_load4<DEV>(rs, prm.off_o + ((base[q] + s0 + j) * D + c4[q] * 4) * 4u)
                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (mine) {
+                        mv[q][j] = own_ml[q];
+                        pv[q][j] = own_o[q];
+                    }
                 }
 #pragma unroll
             for (int q = 0; q < EU; ++q) {
+                if (OWN && q * kAttnThreads >= n_e) continue;
                 float Mn = M[q];
 #pragma unroll
                 for (int j = 0; j < CH; ++j) Mn = fmaxf(Mn, mv[q][j].x);
@@ -252,7 +262,7 @@ __device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buf
 #pragma unroll
         for (int q = 0; q < EU; ++q) {
             if (!ok[q]) continue;
-            const int r = rl[q] / prm.G, hg = rl[q] - r * prm.G;
+            const int r = prm.G == 1 ? rl[q] : (int)__umulhi((unsigned)rl[q], prm.g_magic), hg = rl[q] - r * prm.G;
             const int h = kvh * prm.G + hg;
             const float inv = 1.0f / Lsum[q];  // a row always sees itself: Lsum > 0
             __bf16* op = (__bf16*)prm.O + (long long)b * prm.o_stride_b + (long long)r * prm.o_stride_r +
@@ -267,6 +277,14 @@ __device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buf
                 prm.lse[((long long)b * prm.R + r) * prm.Hq + h] = (M[q] + log2f(Lsum[q])) * 0.69314718055994530942f;
         }
     }
+}
+// the general form: every slot is read from the workspace, two quads and eight slots per round
+template <int D, bool DEV>
+__device__ __forceinline__ void merge_branch(const AttnParams& prm, __amdgpu_buffer_rsrc_t rs, int kvh, int b, int tid,
+                                             int e_begin, int e_end) {
+    const float4 no_o[2] = {};
+    const float2 no_ml[2] = {};
+    merge_branch<D, DEV, 2, 8, false>(prm, rs, kvh, b, tid, e_begin, e_end, -1, no_o, no_ml);
 }
 
 __device__ __forceinline__ bf16x8 load_bf16x8(const __bf16* ptr) {
@@ -528,9 +546,17 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
 
     // ---- combine the 4 wavefronts' states (fixed order) and store the item's partial ----
     // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier all 256
-    // threads form sum_w 2^(m_w - m) O_w for the valid rows and write it out, coalesced.
+    // threads form sum_w 2^(m_w - m) O_w and write the valid rows out, coalesced.  A thread owns QPT
+    // output quads of a row tile -- quad tid + 256 q: the same column of rows RSTEP apart -- and reads
+    // everything it needs for all of them before it uses any of it.
+    constexpr int F4 = D / 4;
+    constexpr int QPT = kRowTile * F4 / kAttnThreads;  // 4 (D = 128) or 2 (D = 64)
+    constexpr int RSTEP = kAttnThreads / F4;
     float* obuf = reinterpret_cast<float*>(lds + wave * SLAB);
     const __amdgpu_buffer_rsrc_t rs = ws_rsrc(prm);
+    const int c4 = tid % F4, row0 = tid / F4;
+    float4 own_o[QPT];    // the last row tile's combined quads, kept for a merge by this workgroup
+    float2 own_ml[QPT];
 #pragma unroll
     for (int t = 0; t < NQT; ++t) {
         if (t > 0) __syncthreads();  // the previous row tile has been read out
@@ -539,46 +565,61 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             sh_m[wave][ln] = m_run[t];
             sh_l[wave][ln] = lsum;
         }
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<float4*>(obuf + ln * OSTRIDE + db * 32 + q4 * 8 + hh * 4) =
-                    make_float4(oacc[t][db][q4 * 4 + 0], oacc[t][db][q4 * 4 + 1], oacc[t][db][q4 * 4 + 2],
-                                oacc[t][db][q4 * 4 + 3]);
-        __syncthreads();
         const int nrows = min(kRowTile, rho_end - (rho0 + t * kRowTile));
-        constexpr int F4 = D / 4;
-        for (int e = tid; e < nrows * F4; e += kAttnThreads) {
-            const int row = e / F4, c4 = e - row * F4;
-            float mw[kAttnWaves], mg = -INFINITY;
+        if (ln < nrows) {  // rows beyond the item's are never read back
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *reinterpret_cast<float4*>(obuf + ln * OSTRIDE + db * 32 + q4 * 8 + hh * 4) =
+                        make_float4(oacc[t][db][q4 * 4 + 0], oacc[t][db][q4 * 4 + 1], oacc[t][db][q4 * 4 + 2],
+                                    oacc[t][db][q4 * 4 + 3]);
+        }
+        __syncthreads();
+        float mw[QPT][kAttnWaves], lw[QPT][kAttnWaves];
+        float4 ov[QPT][kAttnWaves];
+#pragma unroll
+        for (int q = 0; q < QPT; ++q)
 #pragma unroll
             for (int w = 0; w < kAttnWaves; ++w) {
-                mw[w] = sh_m[w][row];
-                mg = fmaxf(mg, mw[w]);
+                if (q * RSTEP >= nrows) continue;  // a whole group of rows beyond the item's (uniform)
+                const int row = min(row0 + q * RSTEP, nrows - 1);
+                mw[q][w] = sh_m[w][row];
+                lw[q][w] = sh_l[w][row];
+                ov[q][w] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(lds + w * SLAB) +
+                                                            row * OSTRIDE + c4 * 4);
             }
+#pragma unroll
+        for (int q = 0; q < QPT; ++q) {
+            if (q * RSTEP >= nrows) continue;
+            const int row = row0 + q * RSTEP;
+            float mg = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kAttnWaves; ++w) mg = fmaxf(mg, mw[q][w]);
             const float mg_use = (mg == -INFINITY) ? 0.f : mg;
             float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
             float lg = 0.f;
 #pragma unroll
             for (int w = 0; w < kAttnWaves; ++w) {
-                const float sc = __builtin_amdgcn_exp2f(mw[w] - mg_use);
-                const float4 v = *reinterpret_cast<const float4*>(
-                    reinterpret_cast<const float*>(lds + w * SLAB) + row * OSTRIDE + c4 * 4);
-                o.x += v.x * sc;
-                o.y += v.y * sc;
-                o.z += v.z * sc;
-                o.w += v.w * sc;
-                lg += sh_l[w][row] * sc;
+                const float sc = __builtin_amdgcn_exp2f(mw[q][w] - mg_use);
+                o.x += ov[q][w].x * sc;
+                o.y += ov[q][w].y * sc;
+                o.z += ov[q][w].z * sc;
+                o.w += ov[q][w].w * sc;
+                lg += lw[q][w] * sc;
             }
-            const unsigned rho = rho0 + t * kRowTile + row;
-            const unsigned pidx = ((unsigned)kvh * prm.B * GR + rho) * pl.nslots + slot;
-            if (pl.fused) {
-                ws_store4<true>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
-                if (c4 == 0) ws_store2<true>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
-            } else {
-                ws_store4<false>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
-                if (c4 == 0) ws_store2<false>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+            own_o[q] = o;
+            own_ml[q] = make_float2(mg, lg);
+            if (row < nrows) {
+                const unsigned rho = rho0 + t * kRowTile + row;
+                const unsigned pidx = ((unsigned)kvh * prm.B * GR + rho) * pl.nslots + slot;
+                if (pl.fused) {
+                    ws_store4<true>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
+                    if (c4 == 0) ws_store2<true>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+                } else {
+                    ws_store4<false>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
+                    if (c4 == 0) ws_store2<false>(rs, prm.off_ml + pidx * 8u, make_float2(mg, lg));
+                }
             }
         }
     }
@@ -611,8 +652,15 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
         sh_last[tid] = last;
     }
     __syncthreads();
-    for (int j = 0; j < nb; ++j)
-        if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
+    // The common shape -- the item's rows are exactly one branch's rows and every partial of the branch
+    // comes from an item like this one -- merges all of the thread's quads in one round of loads and
+    // takes this workgroup's own partial from its registers; everything else goes the general way.
+    if (NQT == 1 && is_private && pl.n_rg_priv == 1 && pl.nsplit_pre == 0) {
+        if (sh_last[0]) merge_branch<D, true, QPT, 2, true>(prm, rs, kvh, b_item, tid, 0, 1 << 30, slot, own_o, own_ml);
+    } else {
+        for (int j = 0; j < nb; ++j)
+            if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
+    }
     __builtin_amdgcn_s_waitcnt(0);
 }
 
@@ -768,6 +816,7 @@ static int launch_attention(const lotts_attn_desc& d, const void* Q, const void*
     prm.O = O; prm.lse = lse;
     prm.B = d.B; prm.k = d.k; prm.R = d.k + 1; prm.Hq = d.Hq; prm.Hkv = d.Hkv; prm.G = d.Hq / d.Hkv;
     prm.GR = prm.G * prm.R; prm.D = d.D; prm.P = d.P; prm.Lmax = d.Lmax;
+    prm.g_magic = (unsigned)((0x100000000ULL + (unsigned)prm.G - 1) / (unsigned)prm.G);  // G = 1 wraps to 0: handled where it is used
     const double scale = d.scale > 0.0f ? (double)d.scale : 1.0 / sqrt((double)d.D);
     prm.scale_log2 = (float)(scale * 1.4426950408889634074);
     prm.q_stride_b = d.q_stride_b; prm.q_stride_r = d.q_stride_r; prm.q_stride_h = d.q_stride_h;
