@@ -142,7 +142,9 @@ size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V);
  *   draft [B][k]  int32 draft tokens in [0, V) (the kernel clamps); NULL iff k == 0
  *   u [B][k+1]    fp32  uniforms in [0, 1)
  *   accept_len [B] int32 out, in [0, k];  next_token [B] int32 out, in [0, V) or -1
- *   workspace: >= spec_accept_workspace_bytes(B, k, V), 8-byte aligned, any contents
+ *   workspace: >= spec_accept_workspace_bytes(B, k, V), 8-byte aligned, any contents (what the kernels
+ *       exchange through it is validated by a tag that differs from call to call)
+ * One launch when V is a multiple of 4, at most 2^18, and the rows are 16-byte aligned; two otherwise.
  */
 int spec_accept(int32_t B, int32_t k, int32_t V, const float *p, const float *q, const int32_t *draft,
                 const float *u, int32_t *accept_len, int32_t *next_token, void *workspace,
@@ -251,7 +253,8 @@ int skinny_gemm(int32_t M, int32_t N, int32_t K, const void *X, int64_t ldx, con
  *       *launches and, if ms is not NULL, each one's milliseconds to ms[0 .. *launches), in launch
  *       order (HOST array of at least max_launches floats).  Switches the timer off.
  * The order of launches inside one call: verify_attention 1 (2 when the partials of a row are
- * many: attention, then merge); spec_accept 2 (scan, pick); spec_accept_logits 4 (max, sum, scan,
+ * many: attention, then merge); spec_accept 1 (2 -- scan, pick -- when V is not a multiple of 4, beyond
+ * 2^18, or the rows are not 16-byte aligned); spec_accept_logits 4 (max, sum, scan,
  * pick); majority_vote 1; confidence_vote 1; skinny_gemm 1 (2 when K is split: GEMM, reduce).
  */
 int lotts_timer_start(int32_t max_launches);

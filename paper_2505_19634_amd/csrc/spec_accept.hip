@@ -1,15 +1,25 @@
 // spec_accept: lossless speculative-sampling acceptance for B branches (the rule of the works
 // the paper cites for speculative decoding in Section 2 / Section 3.2).
 //
-// Two launches, both bound by streaming fp32 rows from HBM:
-//   accept_scan_kernel  grid (chunks, B): every workgroup re-derives the branch's accepted
-//       length n from the 2k gathered probabilities, then turns its chunk of the row to be
-//       sampled (residual max(0, p_n - q_n), or p_k) into 2^-40 fixed-point weights and writes
-//       the chunk's integer sum.  One read of the stop row(s) -- the only V-sized traffic.
-//   accept_pick_kernel  grid (B): scans the chunk sums, locates the chunk and then the token
-//       where the integer CDF crosses T = floor(m * Z / 2^24); re-reads that one chunk only.
+// One launch when the vocabulary fits (accept_fused_kernel), two otherwise:
+//   accept_fused_kernel  grid (S slices x B branches), 4 wavefronts per workgroup.  Every workgroup
+//       re-derives the branch's accepted length n from the 2k gathered probabilities; each of its
+//       wavefronts turns one sub-chunk of the row to be sampled (residual max(0, p_n - q_n), or p_k)
+//       into 2^-40 fixed-point weights -- all of the sub-chunk's loads are requested before the first
+//       is used -- and publishes the sub-chunk's integer sums (residual and plain p) as four 8-byte
+//       words, each carrying half a sum and this call's 32-bit tag.  The workgroup of a branch's LAST
+//       slice then collects the branch's sums (it only ever waits for workgroups with smaller
+//       block indices, which were dispatched before it; the wait is bounded), locates the sub-chunk
+//       and the token where the integer CDF crosses T = floor(m * Z / 2^24), re-reading that one
+//       sub-chunk only, and clears the published words.  One read of the stop row(s) -- the only
+//       V-sized traffic -- and one launch: at these sizes the pass is bound by launch and memory
+//       latency, not by bandwidth.
+//   accept_scan_kernel + accept_pick_kernel  (V not a multiple of 4, unaligned rows, V > 2^18):
+//       grid (chunks, B) writes chunk sums; a second launch (B) picks.
 // All sums are 64-bit integers, so the result is independent of reduction order and equals a
 // sequential scan bit for bit.
+#include <atomic>
+
 #include "lotts_common.h"
 
 namespace lotts {
@@ -259,12 +269,268 @@ __global__ __launch_bounds__(kAccThreads) void accept_pick_kernel(int B, int k, 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// single-launch path
+// ---------------------------------------------------------------------------------------------
+constexpr int kFuMaxSub = 64;        // sub-chunks per branch (one wavefront each): one wavefront scans their sums
+constexpr int kFuMaxIter = 16;       // 16-byte loads per row and lane: sub-chunks of at most 4096 tokens
+constexpr int kFuMaxV = kFuMaxSub * kFuMaxIter * 256;
+constexpr int kFuSpinLimit = 1 << 18;  // polls of the collecting workgroup before it gives up (far beyond any real wait)
+
+struct FusedPlan {
+    int wlen;    // tokens per sub-chunk, a multiple of 256
+    int iters;   // wlen / 256: 16-byte loads per row and lane, and tokens per thread in the pick
+    int nsub;    // sub-chunks that hold tokens, <= kFuMaxSub
+    int S;       // workgroups (slices of 4 sub-chunks) per branch
+};
+static inline FusedPlan plan_fused(int V) {
+    FusedPlan pl;
+    pl.wlen = ((V + kFuMaxSub - 1) / kFuMaxSub + 255) / 256 * 256;
+    pl.iters = pl.wlen / 256;
+    pl.nsub = (V + pl.wlen - 1) / pl.wlen;
+    pl.S = (pl.nsub + kAccWaves - 1) / kAccWaves;
+    return pl;
+}
+
+// trunc(r * 2^40) for 0 <= r <= 1 as two 32-bit conversions: hi = floor(r * 2^16), lo = floor(frac(r * 2^16) * 2^24);
+// every step is exact (power-of-two scalings, fract), and hi * 2^24 + lo is the same integer as fixed_weight(r).
+__device__ __forceinline__ void fixed_weight_split(float r, unsigned& hi, unsigned& lo) {
+    const float a = fmaxf(r, 0.0f) * 65536.0f;  // negative and NaN inputs weigh nothing, as in fixed_weight
+    hi = (unsigned)a;
+    lo = (unsigned)(__builtin_amdgcn_fractf(a) * 16777216.0f);
+}
+
+// Sum over the wavefront of hi * 2^24 + lo with hi < 2^26 and lo < 2^30 per lane: the carry of lo moves into hi first, then
+// both halves are summed as 32-bit values in two independent shuffle chains.  The total is valid in lane 0.
+__device__ __forceinline__ unsigned long long wave_sum_split(unsigned hi, unsigned lo) {
+    hi += lo >> 24;
+    lo &= 0xffffffu;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        hi += __shfl_down(hi, d, kWave);
+        lo += __shfl_down(lo, d, kWave);
+    }
+    return ((unsigned long long)hi << 24) + lo;
+}
+// Inclusive prefix sum over the wavefront of values below 2^58, as three limbs of 24 bits in independent 32-bit chains
+// (a 64-bit shuffle chain costs twice the dependent steps).
+__device__ __forceinline__ unsigned long long wave_incl_scan_limbs(unsigned long long v, int lane) {
+    unsigned l0 = (unsigned)v & 0xffffffu, l1 = (unsigned)(v >> 24) & 0xffffffu, l2 = (unsigned)(v >> 48);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const unsigned o0 = __shfl_up(l0, d, kWave), o1 = __shfl_up(l1, d, kWave), o2 = __shfl_up(l2, d, kWave);
+        if (lane >= d) {
+            l0 += o0;
+            l1 += o1;
+            l2 += o2;
+        }
+    }
+    return (unsigned long long)l0 + ((unsigned long long)l1 << 24) + ((unsigned long long)l2 << 48);
+}
+
+// one published word: half of a 64-bit sum under the call's tag
+__device__ __forceinline__ unsigned long long tagged(unsigned half, unsigned tag) {
+    return ((unsigned long long)tag << 32) | half;
+}
+__device__ __forceinline__ void publish(unsigned long long* slot, unsigned long long v) {
+    __hip_atomic_store(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long peek(const unsigned long long* slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The row a branch samples when its residual has no mass at all (only possible when a draft of probability zero under
+// both models was "rejected", or for rows that are not distributions): the row p_n itself, handled by the collecting
+// workgroup alone.  Thread t owns the tokens [t * E, (t + 1) * E); slow, and never on the path of a real workload.
+__device__ __noinline__ int pick_plain_row(const float* __restrict__ prow, int V, unsigned m, unsigned long long* sh_scan) {
+    const int tid = threadIdx.x;
+    const int E = (V + kAccThreads - 1) / kAccThreads;
+    const int lo = tid * E, hi = min(V, lo + E);
+    unsigned long long local = 0;
+    for (int i = lo; i < hi; ++i) local += fixed_weight(prow[i]);
+    __shared__ unsigned long long sh_total;
+    const unsigned long long excl = block_excl_scan(local, sh_scan);
+    if (tid == kAccThreads - 1) sh_total = excl + local;
+    __syncthreads();
+    const unsigned long long Z = sh_total;
+    if (Z == 0) return -1;
+    const unsigned long long T = (__umul64hi((unsigned long long)m, Z) << 40) | (((unsigned long long)m * Z) >> 24);
+    __shared__ int sh_tok;
+    if (excl <= T && T < excl + local) {  // exactly one thread
+        unsigned long long run = excl;
+        int tok = lo;
+        for (int i = lo; i < hi; ++i) {
+            run += fixed_weight(prow[i]);
+            if (run > T) {
+                tok = i;
+                break;
+            }
+        }
+        sh_tok = tok;
+    }
+    __syncthreads();
+    return sh_tok;
+}
+
+template <int MAXIT>
+__global__ __launch_bounds__(kAccThreads) void accept_fused_kernel(int B, int k, int V, FusedPlan pl, unsigned tag,
+                                                                   const float* __restrict__ p,
+                                                                   const float* __restrict__ q,
+                                                                   const int32_t* __restrict__ draft,
+                                                                   const float* __restrict__ u,
+                                                                   int32_t* __restrict__ accept_len,
+                                                                   int32_t* __restrict__ next_token,
+                                                                   unsigned long long* __restrict__ slots) {
+    __shared__ int sh_first[kAccWaves];
+    __shared__ unsigned long long sh_scan[kAccWaves];
+    __shared__ unsigned long long sh_base, sh_T;
+    __shared__ int sh_chunk, sh_bad;
+    const int b = blockIdx.x / pl.S, s = blockIdx.x - b * pl.S;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int n = accepted_length(b, k, V, p, q, draft, u, sh_first);
+
+    // the row to sample: weights max(0, p_n - q_n) after a rejection, p_k when every draft was accepted
+    const float* prow = p + ((size_t)b * (k + 1) + n) * V;
+    const bool has_q = n < k;
+    const float* qrow = has_q ? q + ((size_t)b * k + n) * V : prow;
+    const int sub = s * kAccWaves + wave;          // this wavefront's sub-chunk of the row
+    const int lo = sub * pl.wlen;
+    // all of the sub-chunk is requested before any of it is used
+    float4 pv[MAXIT], qv[MAXIT];
+#pragma unroll
+    for (int i = 0; i < MAXIT; ++i) {
+        const int idx = lo + (i * kWave + lane) * 4;
+        const bool in = i < pl.iters && idx < V;   // V is a multiple of 4 here: a group is inside or outside as a whole
+        pv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        qv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (in) pv[i] = *reinterpret_cast<const float4*>(prow + idx);
+        if (in && has_q) qv[i] = *reinterpret_cast<const float4*>(qrow + idx);
+    }
+    // per lane: at most 64 weights; their high parts (<= 2^16) and low parts (< 2^24) add up in 32 bits
+    unsigned w_hi = 0, w_lo = 0;
+#pragma unroll
+    for (int i = 0; i < MAXIT; ++i) {
+        const float pe[4] = {pv[i].x, pv[i].y, pv[i].z, pv[i].w};
+        const float qe[4] = {qv[i].x, qv[i].y, qv[i].z, qv[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            unsigned h, l;
+            fixed_weight_split(has_q ? residual(pe[e], qe[e]) : pe[e], h, l);
+            w_hi += h;
+            w_lo += l;
+        }
+    }
+    const unsigned long long s_sub = wave_sum_split(w_hi, w_lo);
+    unsigned long long* mine = slots + ((size_t)b * kFuMaxSub + sub) * 2;
+    if (lane == 0 && sub < pl.nsub) {
+        publish(mine + 0, tagged((unsigned)s_sub, tag));
+        publish(mine + 1, tagged((unsigned)(s_sub >> 32), tag));
+    }
+    if (s != pl.S - 1) return;  // uniform over the workgroup
+
+    // ---- the branch's last slice collects: it waits only for workgroups dispatched before it ----
+    if (tid == 0) {
+        accept_len[b] = n;
+        sh_bad = 0;
+    }
+    __syncthreads();
+    unsigned m = (unsigned)(u[(size_t)b * (k + 1) + k] * 16777216.0f);  // trunc(u * 2^24)
+    m = m > 16777215u ? 16777215u : m;                                  // u must be < 1; keep T < Z regardless
+    if (wave == 0) {
+        unsigned long long v = 0;
+        if (lane < pl.nsub) {
+            unsigned long long* e = slots + ((size_t)b * kFuMaxSub + lane) * 2;
+            unsigned long long w0 = 0, w1 = 0;
+            bool ok = false;
+            for (int spin = 0; spin < kFuSpinLimit; ++spin) {
+                w0 = peek(e + 0);
+                w1 = peek(e + 1);
+                ok = (unsigned)(w0 >> 32) == tag && (unsigned)(w1 >> 32) == tag;
+                if (ok) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (!ok) sh_bad = 1;  // never seen in practice: the producers were dispatched first and wait for nothing
+            v = ((w1 & 0xffffffffull) << 32) | (w0 & 0xffffffffull);
+            // the words are consumed: clear them, so that a captured launch (same tag) can be replayed
+            publish(e + 0, 0ull);
+            publish(e + 1, 0ull);
+        }
+        const unsigned long long incl = wave_incl_scan_limbs(v, lane);
+        const unsigned long long Z = shfl_u64(incl, kWave - 1);
+        const unsigned long long T = (__umul64hi((unsigned long long)m, Z) << 40) | (((unsigned long long)m * Z) >> 24);
+        if (lane == 0) {
+            sh_chunk = Z == 0 ? -1 : -2;  // -1: no mass in these weights; -2 is replaced by the lane that holds the crossing
+            sh_T = T;
+        }
+        if (Z != 0 && incl - v <= T && T < incl) {  // exactly one lane: T < Z
+            sh_chunk = lane;                        // after lane 0's store in the wavefront's program order
+            sh_base = incl - v;
+        }
+    }
+    __syncthreads();
+    int c = sh_chunk;
+    if (sh_bad) c = -3;
+    if (c == -1 && has_q) {  // empty residual: the row p_n itself is sampled (uniform over the workgroup)
+        const int tok = pick_plain_row(prow, V, m, sh_scan);
+        if (tid == 0) next_token[b] = tok;
+        return;
+    }
+    if (c < 0) {
+        if (tid == 0) next_token[b] = -1;
+        return;
+    }
+    const unsigned long long base = sh_base, T = sh_T;
+
+    // inside the sub-chunk: thread t owns pl.iters consecutive tokens (served by the caches: just streamed)
+    const int lo2 = c * pl.wlen + tid * pl.iters;
+    float pw[MAXIT], qw[MAXIT];
+#pragma unroll
+    for (int i = 0; i < MAXIT; ++i) {
+        const bool in = i < pl.iters && lo2 + i < V;
+        pw[i] = in ? prow[lo2 + i] : 0.f;
+        qw[i] = (in && has_q) ? qrow[lo2 + i] : 0.f;
+    }
+    unsigned long long w[MAXIT], local = 0;
+#pragma unroll
+    for (int i = 0; i < MAXIT; ++i) {
+        unsigned h, l;
+        fixed_weight_split(has_q ? residual(pw[i], qw[i]) : pw[i], h, l);
+        w[i] = ((unsigned long long)h << 24) + l;
+        local += w[i];
+    }
+    // exclusive prefix over the workgroup in thread order
+    const unsigned long long incl = wave_incl_scan_limbs(local, lane);
+    if (lane == kWave - 1) sh_scan[wave] = incl;
+    __syncthreads();
+    unsigned long long run = base + incl - local;
+#pragma unroll
+    for (int i = 0; i < kAccWaves; ++i) run += (i < wave) ? sh_scan[i] : 0ull;
+    if (run <= T && T < run + local) {
+        int tok = lo2;
+        unsigned long long pre = run;
+        bool found = false;
+#pragma unroll
+        for (int i = 0; i < MAXIT; ++i) {  // the first i whose inclusive prefix exceeds T
+            pre += w[i];
+            if (!found && pre > T) {
+                tok = lo2 + i;
+                found = true;
+            }
+        }
+        next_token[b] = tok;
+    }
+}
+
+static std::atomic<unsigned> g_accept_tag{0};
+
 }  // namespace lotts
 
 extern "C" size_t spec_accept_workspace_bytes(int32_t B, int32_t k, int32_t V) {
     if (B < 1 || k < 0 || k > lotts::kAccMaxK || V < 1 || B > 65535) return 0;
     const lotts::AcceptPlan pl = lotts::plan_accept(V);
-    return (size_t)2 * B * pl.nchunks * sizeof(unsigned long long);
+    const size_t two_launch = (size_t)2 * B * pl.nchunks * sizeof(unsigned long long);
+    const size_t one_launch = (size_t)B * lotts::kFuMaxSub * 2 * sizeof(unsigned long long);
+    return two_launch > one_launch ? two_launch : one_launch;  // the call picks the path from V and the pointers
 }
 
 extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, const float* q, const int32_t* draft,
@@ -281,6 +547,25 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
     hipStream_t s = (hipStream_t)stream;
     // float4 loads need every row start 16-byte aligned
     const bool vec = (V % 4 == 0) && (((uintptr_t)p & 15) == 0) && (k == 0 || ((uintptr_t)q & 15) == 0);
+    if (vec && V <= kFuMaxV) {  // one launch
+        const FusedPlan fp = plan_fused(V);
+        unsigned tag = g_accept_tag.fetch_add(1, std::memory_order_relaxed) + 1;
+        if (tag == 0) tag = g_accept_tag.fetch_add(1, std::memory_order_relaxed) + 1;  // 0 is what cleared words hold
+        const dim3 fgrid((unsigned)((long long)B * fp.S));
+        if (fp.iters <= 4)
+            LOTTS_LAUNCH(accept_fused_kernel<4>, fgrid, dim3(kAccThreads), s, B, k, V, fp, tag, p, q, draft, u, accept_len,
+                         next_token, sums);
+        else if (fp.iters <= 8)
+            LOTTS_LAUNCH(accept_fused_kernel<8>, fgrid, dim3(kAccThreads), s, B, k, V, fp, tag, p, q, draft, u, accept_len,
+                         next_token, sums);
+        else if (fp.iters <= 12)
+            LOTTS_LAUNCH(accept_fused_kernel<12>, fgrid, dim3(kAccThreads), s, B, k, V, fp, tag, p, q, draft, u, accept_len,
+                         next_token, sums);
+        else
+            LOTTS_LAUNCH(accept_fused_kernel<16>, fgrid, dim3(kAccThreads), s, B, k, V, fp, tag, p, q, draft, u, accept_len,
+                         next_token, sums);
+        return check_launch();
+    }
     const dim3 grid(pl.nchunks, B);
     if (vec)
         LOTTS_LAUNCH(accept_scan_kernel<true>, grid, dim3(kAccThreads), s, B, k, V, pl.chunk, pl.nchunks, p,
