@@ -7,12 +7,19 @@ HBM before the timed region; several independent input sets are rotated so that 
 memory-side cache cannot serve the KV stream.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--sets 4]
+
+Beside the contract's fields the line carries: `roofline` (the attention kernel against the HBM peak, timed by
+event pairs attached to its launches, with the statistics of the sample and a read-only streaming probe over
+the same buffers as the ceiling of this machine), `layers_back_to_back` (the amortised per-layer figure: one
+verify_attention call per decoder layer, launched back to back over rotated inputs), and `cpu_baseline`
+(the CPU oracle on the same inputs on this machine's host cores).
 """
 from __future__ import annotations
 
 import argparse
 import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -58,8 +65,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", help="C2, C3, C5 or C4xB (e.g. C4x16)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--torch-sdpa", action="store_true",
-                    help="also time torch on the same problems: scaled_dot_product_attention and linear (context only)")
+    ap.add_argument("--min-timed-launches", type=int, default=64,
+                    help="attention launches timed in all (timed region plus a labelled leg after it)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path shards by branch with no "
@@ -156,7 +163,11 @@ def main() -> int:
         if rc != 0:
             raise RuntimeError("a lotts call failed (status %d)" % rc)
 
-    for i in range(args.warmup):
+    # The first launches of a process run on a GPU that is still at idle clocks (measured: up to 63 us for the
+    # attention kernel instead of 46).  SETTLE untimed steps bring it to its running state whatever --warmup is;
+    # the W warm-up steps of the contract follow.
+    SETTLE = 200
+    for i in range(SETTLE + args.warmup):
         step(i)
     torch.cuda.synchronize()
 
@@ -164,7 +175,9 @@ def main() -> int:
     # verify_attention call of every 8th step: its launch carries its own HIP event pair on the launch
     # stream, which reads the kernel's start and end on the device (the dominant kernel's launch
     # duration, without the gaps that event records around a call would add).  A timed launch costs the
-    # queue about 7 us more than a plain one, hence not every step.
+    # queue about 7 us more than a plain one, hence not every step.  After the region the same pattern of
+    # steps (one timed, seven plain) goes on until --min-timed-launches launches have been timed in all, so
+    # that the roofline figure rests on a sample of that size whatever K is.
     K = args.steps
     EVERY = 8
     n_launch = ctypes.c_int32()
@@ -172,30 +185,47 @@ def main() -> int:
     lib.verify_attention(*calls[0][0])
     assert lib.lotts_timer_stop(ctypes.byref(n_launch), None) == 0
     attn_launches = n_launch.value                     # 1, or 2 when a second launch merges the partials
-    n_timed = (K + EVERY - 1) // EVERY
-    kernel_ms = (ctypes.c_float * (n_timed * attn_launches))()
-    torch.cuda.synchronize()
-    assert lib.lotts_timer_start(n_timed * attn_launches) == 0
-    lib.lotts_timer_pause(1)
-    t0 = time.perf_counter()
-    for i in range(K):
-        if i % EVERY == 0:
-            attn_args, acc_args, vote_args = calls[i % nsets]
-            lib.lotts_timer_pause(0)
-            rc = lib.verify_attention(*attn_args)
-            lib.lotts_timer_pause(1)
-            rc |= lib.spec_accept(*acc_args)
-            rc |= lib.majority_vote(*vote_args)
-            if rc != 0:
-                raise RuntimeError("a lotts call failed (status %d)" % rc)
-        else:
-            step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    assert lib.lotts_timer_stop(ctypes.byref(n_launch), kernel_ms) == 0 and n_launch.value == n_timed * attn_launches
+
+    def steps_with_sampling(first, count):
+        """`count` steps starting at step number `first`; every EVERYth carries the timer.  Returns (kernel ms of
+        the timed launches in launch order, host clock before the first step, host clock after the device has
+        finished the last)."""
+        n_t = (count + EVERY - 1) // EVERY
+        buf = (ctypes.c_float * (n_t * attn_launches))()
+        assert lib.lotts_timer_start(n_t * attn_launches) == 0     # creates its events on first use: before the clock starts
+        lib.lotts_timer_pause(1)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for i in range(first, first + count):
+            if (i - first) % EVERY == 0:
+                attn_args, acc_args, vote_args = calls[i % nsets]
+                lib.lotts_timer_pause(0)
+                rc = lib.verify_attention(*attn_args)
+                lib.lotts_timer_pause(1)
+                rc |= lib.spec_accept(*acc_args)
+                rc |= lib.majority_vote(*vote_args)
+                if rc != 0:
+                    raise RuntimeError("a lotts call failed (status %d)" % rc)
+            else:
+                step(i)
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        got = ctypes.c_int32()
+        assert lib.lotts_timer_stop(ctypes.byref(got), buf) == 0 and got.value == n_t * attn_launches
+        return list(buf), t_begin, t_end
+
+    kernel_ms, t0, t1 = steps_with_sampling(0, K)
     ms_per_step = (t1 - t0) * 1e3 / K
-    attn_ms = sum(kernel_ms[0::attn_launches]) / n_timed        # attn_kernel: the launch that streams K and V
+    n_in_region = len(kernel_ms) // attn_launches
+    extra_steps = max(0, args.min_timed_launches - n_in_region) * EVERY
+    if extra_steps:
+        more, _, _ = steps_with_sampling(K, extra_steps)
+        kernel_ms += more
+    attn_samples = sorted(kernel_ms[0::attn_launches])   # attn_kernel: the launch that streams K and V
+    n_timed = len(attn_samples)
+    attn_ms = sum(attn_samples) / n_timed
     merge_ms = sum(kernel_ms[1::attn_launches]) / n_timed if attn_launches == 2 else 0.0
+    in_region = kernel_ms[0:n_in_region * attn_launches:attn_launches]
 
     # ---- outside the timed region: the same K steps with the timer off (what the event pairs cost the step),
     # and verify_attention calls bracketed by event records on the stream (gaps around the call included)
@@ -221,22 +251,55 @@ def main() -> int:
     torch.cuda.synchronize()
     acc_ms = sum(e[1].elapsed_time(e[2]) for e in ev4) / K2
     vote_ms = sum(e[2].elapsed_time(e[3]) for e in ev4) / K2
-    eb = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    eb[0].record(stream)
-    for i in range(K2):
-        lib.verify_attention(*calls[i % nsets][0])
-    eb[1].record(stream)
-    torch.cuda.synchronize()
-    attn_ms_b2b = eb[0].elapsed_time(eb[1]) / K2
+    # the amortised figure: one verify_attention call per decoder layer of the model the shape stands for,
+    # launched back to back over the rotated inputs, between two event records
+    n_layers = 64 if cfg.Hkv == 8 else 36
+    layer_ms = []
+    for rep in range(3):
+        eb = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        eb[0].record(stream)
+        for i in range(n_layers):
+            lib.verify_attention(*calls[i % nsets][0])
+        eb[1].record(stream)
+        torch.cuda.synchronize()
+        layer_ms.append(eb[0].elapsed_time(eb[1]) / n_layers)
+    attn_ms_b2b = sorted(layer_ms)[1]
 
     # cache-resident variant for comparison: one input set only
-    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(min(K, 100))]
+    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(min(K, 50))]
     for e in ev2:
         e[0].record(stream)
         lib.verify_attention(*calls[0][0])
         e[1].record(stream)
     torch.cuda.synchronize()
     attn_ms_resident = sum(e[0].elapsed_time(e[1]) for e in ev2) / len(ev2)
+
+    # the ceiling of this machine: a kernel that only reads the same K and V buffers (rotated in the same way), launched in
+    # the attention kernel's shape and timed in the same way (event pair attached to the dispatch)
+    probe_path = os.path.join(ROOT, "paper_2505_19634_amd", "libread_probe.so")
+    read_ceiling = None
+    if bf and os.path.exists(probe_path):
+        probe = ctypes.CDLL(probe_path)
+        probe.read_probe.restype = ctypes.c_int
+        probe.read_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.POINTER(ctypes.c_float)]
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        kv_bytes = sets[0]["Kpriv"].numel() * sets[0]["Kpriv"].element_size()
+        pm = ctypes.c_float()
+        probe_ms = []
+        for i in range(8 + 64):
+            d = sets[i % nsets]
+            rc = probe.read_probe(d["Kpriv"].data_ptr(), d["Vpriv"].data_ptr(), kv_bytes, sink.data_ptr(), sh, ctypes.byref(pm))
+            if rc != 0:
+                raise RuntimeError("read_probe failed")
+            if i >= 8:
+                probe_ms.append(pm.value)
+        probe_ms.sort()
+        probe_bytes = 2 * (kv_bytes // 8192) * 8192
+        read_ceiling = {"bytes_per_launch": probe_bytes, "launches": len(probe_ms),
+                        "avg_launch_ms": sum(probe_ms) / len(probe_ms), "median_launch_ms": probe_ms[len(probe_ms) // 2],
+                        "min_launch_ms": probe_ms[0], "max_launch_ms": probe_ms[-1],
+                        "GB/s": probe_bytes / (sum(probe_ms) / len(probe_ms) * 1e-3) / 1e9}
 
     tokens = cfg.B * cfg.R
     n0 = sets[0]["accept_len"].cpu().numpy()
@@ -248,7 +311,8 @@ def main() -> int:
         "metric": "verified branch-tokens/sec per verify step",
         "value": tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "untimed_settle_steps_before_warmup": SETTLE,
+        "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "%s: B=%d k=%d Hq=%d Hkv=%d D=%d prefix=%d private=%d V=%d, 1 layer; step = "
@@ -261,16 +325,36 @@ def main() -> int:
                                                      "streams K and V; attn_merge_kernel follows"),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary committed under profiles/ (counters "
+                                       "cannot be read from inside this process)",
                      "algorithmic_bytes_per_launch": bytes_attn, "avg_launch_ms": attn_ms, "launches_timed": n_timed,
-                     "timing": "HIP event pair attached to the dispatch, every %dth step of the timed region" % EVERY,
+                     "launch_ms": {"min": attn_samples[0], "median": attn_samples[n_timed // 2], "mean": attn_ms,
+                                   "max": attn_samples[-1]},
+                     "launches_timed_inside_timed_region": n_in_region,
+                     "avg_launch_ms_inside_timed_region": sum(in_region) / len(in_region),
+                     "frac_at_median": bytes_attn / (attn_samples[n_timed // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "timing": "HIP event pair attached to the dispatch; the verify_attention launch of every %dth step, in the "
+                               "timed region and in the same pattern of steps after it" % EVERY,
+                     "read_ceiling_GBs": None if read_ceiling is None else read_ceiling["GB/s"],
+                     "frac_of_read_ceiling": None if read_ceiling is None else achieved / read_ceiling["GB/s"],
+                     "read_ceiling": read_ceiling,
                      "avg_merge_launch_ms": merge_ms,
                      "avg_call_ms_event_records_around_call": attn_ms_bracket,
                      "avg_call_ms_single_set_cache_resident": attn_ms_resident,
                      "avg_call_ms_back_to_back": attn_ms_b2b},
+        "layers_back_to_back": {"layers": n_layers, "ms_per_layer": attn_ms_b2b,
+                                "GB/s": bytes_attn / (attn_ms_b2b * 1e-3) / 1e9,
+                                "frac_of_hbm_peak": bytes_attn / (attn_ms_b2b * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "note": "verify_attention only, one call per layer back to back over rotated inputs, median of "
+                                        "3 runs; launch gaps included"},
         "breakdown_ms": {"verify_attention": attn_ms_bracket, "spec_accept": acc_ms, "majority_vote": vote_ms},
         "spec_accept": {"algorithmic_bytes": bytes_acc, "GB/s": bytes_acc / (acc_ms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": bytes_acc / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "mean_accepted": float(n0.mean()),
+                        "acceptance_rate_sum_min_p_q": (None if cfg.k == 0 else
+                                                        float(np.minimum(s0["p"][:, :cfg.k], s0["q"]).sum(-1).mean())),
+                        "acceptance_rate_closed_form": (None if (cfg.k == 0 or not cfg.noise_std) else
+                                                        float(math.erfc(cfg.noise_std / 2.0 / math.sqrt(2.0)))),
                         "emitted_tokens_per_s": float((n0 + 1).sum()) / (ms_per_step * 1e-3)},
     }
 
@@ -353,46 +437,6 @@ def main() -> int:
         del Ws, Xg, Yg, wsg
     out["skinny_gemm"] = gemms
 
-    # ---- context only, on request: the attention problem handed to torch's scaled_dot_product_attention.  It has no
-    # shared-prefix form and no bottom-right causal mode, so the prefix is replicated per branch and the mask is explicit.
-    if args.torch_sdpa and bf:
-        import torch.nn.functional as F
-        Sx = cfg.P + cfg.L
-        tq = [d["Q"].permute(0, 2, 1, 3).contiguous() for d in sets]
-        tk = [torch.cat([d["Kpre"][None].expand(cfg.B, -1, -1, -1), d["Kpriv"]], dim=2).contiguous() for d in sets]
-        tv = [torch.cat([d["Vpre"][None].expand(cfg.B, -1, -1, -1), d["Vpriv"]], dim=2).contiguous() for d in sets]
-        mask = torch.ones(cfg.R, Sx, dtype=torch.bool, device=dev).tril(diagonal=Sx - cfg.R)
-        sdpa = lambda i: F.scaled_dot_product_attention(tq[i % nsets], tk[i % nsets], tv[i % nsets], attn_mask=mask,
-                                                        enable_gqa=True)
-        for i in range(4):
-            sdpa(i)
-        eb2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        eb2[0].record(stream)
-        for i in range(20):
-            sdpa(i)
-        eb2[1].record(stream)
-        torch.cuda.synchronize()
-        out["torch_sdpa_context"] = {"ms_back_to_back": eb2[0].elapsed_time(eb2[1]) / 20,
-                                     "note": "prefix replicated per branch, boolean mask, enable_gqa; torch " + torch.__version__}
-        del tq, tk, tv
-        # the four weight GEMMs through torch.nn.functional.linear (the vendor GEMM library), same shapes and M
-        lin = {}
-        for name_, (Ng, Kg) in {"qkv_proj": (7168, 5120), "o_proj": (5120, 5120), "gate_up_proj": (55296, 5120),
-                                "down_proj": (5120, 27648)}.items():
-            Ws = [(torch.randn((Ng, Kg), generator=gen, device=dev) * Kg ** -0.5).to(torch.bfloat16) for _ in range(3)]
-            Xg = torch.randn((Mg, Kg), generator=gen, device=dev).to(torch.bfloat16)
-            for i in range(4):
-                F.linear(Xg, Ws[i % 3])
-            el = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            el[0].record(stream)
-            for i in range(20):
-                F.linear(Xg, Ws[i % 3])
-            el[1].record(stream)
-            torch.cuda.synchronize()
-            lin[name_] = el[0].elapsed_time(el[1]) / 20
-            del Ws, Xg
-        out["torch_linear_context"] = {"M": Mg, "ms_back_to_back": lin}
-
     # ---- the CPU oracle on the same inputs (set 0), on this machine's host cores: a baseline, not the target
     if not args.no_cpu_baseline:
         import oracle
@@ -405,8 +449,16 @@ def main() -> int:
             oracle.majority_vote(answers0)
             t_cpu += time.perf_counter() - c0
             reps += 1
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": tokens * reps / t_cpu, "unit": "tokens/s", "cores": oracle.n_threads(),
-                               "kind": "oracle",
+                               "kind": "oracle", "cpu_model": cpu_model,
                                "sample": "%d full steps of the same workload (input set 0), fp64, OpenMP over "
                                          "(branch, head)" % reps}
         # the same on one thread (a shorter sample: about 5 s)

@@ -9,6 +9,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblotts.so")
 CALIB = os.path.join(_HERE, "calib_copy")
+PROBE = os.path.join(_HERE, "libread_probe.so")
 SOURCES = ["verify_attention.hip", "spec_accept.hip", "spec_accept_logits.hip", "majority_vote.hip",
            "confidence_vote.hip", "skinny_gemm.hip", "kernel_timer.hip", "greedy_search.cpp"]
 
@@ -30,6 +31,12 @@ def build(verbose: bool = False) -> str:
     # the counter-calibration copy program (profiling aid, not part of the library)
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", os.path.join(CSRC, "calib_copy.hip"), "-o", CALIB]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    # the read-only streaming probe bench.py puts next to the attention kernel (measurement aid, its own library)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", os.path.join(CSRC, "read_probe.hip"), "-o", PROBE]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
