@@ -254,8 +254,8 @@ int skinny_gemm(int32_t M, int32_t N, int32_t K, const void *X, int64_t ldx, con
  *       order (HOST array of at least max_launches floats).  Switches the timer off.
  * The order of launches inside one call: verify_attention 1 (2 when the partials of a row are
  * many: attention, then merge); spec_accept 1 (2 -- scan, pick -- when V is not a multiple of 4, beyond
- * 2^18, or the rows are not 16-byte aligned); spec_accept_logits 4 (max, sum, scan,
- * pick); majority_vote 1; confidence_vote 1; skinny_gemm 1 (2 when K is split: GEMM, reduce).
+ * 2^18, or the rows are not 16-byte aligned); spec_accept_logits 3 (max, sum,
+ * scan and pick); majority_vote 1; confidence_vote 1; skinny_gemm 1 (2 when K is split: GEMM, reduce).
  */
 int lotts_timer_start(int32_t max_launches);
 int lotts_timer_pause(int32_t paused);

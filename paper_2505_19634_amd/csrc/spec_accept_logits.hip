@@ -12,13 +12,18 @@
 // U = trunc(u * 2^24); residual weights W_v = max(0, Ep_v * Sq - Eq_v * Sp); bonus weights Ep_v;
 // token = first v whose prefix sum exceeds floor(U_k * sum W / 2^24).  128-bit integers.
 //
-// Four launches:
+// Three launches:
 //   lg_max_kernel, lg_sum_kernel   grid (pieces of 16384 logits, B * (2k + 1) rows): piece maxima, then --
 //                       with the row maximum known -- the pieces' integer weight sums, added into one
 //                       64-bit sum per row with device-scope atomics (integers: any order gives the same
 //                       sum); the second sweep of the logits is served by the L2 / memory-side cache.
-//   lg_scan_kernel      grid (chunks, B): accept tests -> n; 128-bit chunk sums of the weights of row n.
-//   lg_pick_kernel      grid (B): chunk and token where the integer CDF crosses the threshold.
+//   lg_scan_pick_kernel grid (chunks, B): accept tests -> n; 128-bit chunk sums of the weights of row n, published as
+//                       six 8-byte words that each carry 32 bits of a sum and this call's tag.  The workgroup of a
+//                       branch's LAST chunk then collects the branch's sums (it waits only for workgroups with smaller
+//                       block indices, dispatched before it; the wait is bounded) and finds the chunk and the token
+//                       where the integer CDF crosses the threshold, re-reading that one chunk.
+#include <atomic>
+
 #include "lotts_common.h"
 
 namespace lotts {
@@ -340,21 +345,36 @@ __device__ __forceinline__ void lg_weights8(const void* zt_row, const void* zd_r
     }
 }
 
+constexpr int kLgSpinLimit = 1 << 18;  // polls of the collecting workgroup before it gives up (far beyond any real wait)
+
+// one published word: 32 bits of a sum under the call's tag
+__device__ __forceinline__ void lg_publish(unsigned long long* slot, unsigned part, unsigned tag) {
+    __hip_atomic_store(slot, ((unsigned long long)tag << 32) | part, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long lg_peek(const unsigned long long* slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kLgThreads) void lg_scan_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
-                                                             const void* __restrict__ zd, float inv_temp,
-                                                             const int32_t* __restrict__ draft,
-                                                             const float* __restrict__ u,
-                                                             const float* __restrict__ rmax,
-                                                             const unsigned long long* __restrict__ rsum,
-                                                             int32_t* __restrict__ accept_len, u128* __restrict__ wsum,
-                                                             unsigned long long* __restrict__ psum) {
+__global__ __launch_bounds__(kLgThreads) void lg_scan_pick_kernel(int B, int k, int V, int nchunks, unsigned tag,
+                                                                  const void* __restrict__ zt, const void* __restrict__ zd,
+                                                                  float inv_temp, const int32_t* __restrict__ draft,
+                                                                  const float* __restrict__ u,
+                                                                  const float* __restrict__ rmax,
+                                                                  const unsigned long long* __restrict__ rsum,
+                                                                  int32_t* __restrict__ accept_len,
+                                                                  unsigned long long* __restrict__ slots,  // [B][nchunks][6]
+                                                                  int32_t* __restrict__ next_token,
+                                                                  int32_t* __restrict__ priv_len) {
     __shared__ int sh_first[kLgWaves];
     __shared__ u128 sh_w[kLgWaves];
+    __shared__ u128 sh_base;
+    __shared__ int sh_chunk, sh_bad;
+    __shared__ u128 sh_wsum[kLgMaxChunks];
+    __shared__ unsigned long long sh_psum[kLgMaxChunks];
     const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
     const int n = lg_accepted_length<BF16>(B, b, k, V, zt, zd, inv_temp, draft, u, rmax, rsum, sh_first);
-    if (c == 0 && tid == 0) accept_len[b] = n;
-    const bool residual = n < k;
+    bool residual = n < k;
     const size_t es = BF16 ? 2 : 4;
     const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
     const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
@@ -371,50 +391,66 @@ __global__ __launch_bounds__(kLgThreads) void lg_scan_kernel(int B, int k, int V
     }
     w = block_sum_u128(w, sh_w);
     e = block_sum_u128(e, sh_w);
+    unsigned long long* mine = slots + ((size_t)b * nchunks + c) * 6;
     if (tid == 0) {
-        wsum[(size_t)b * nchunks + c] = w;
-        psum[(size_t)b * nchunks + c] = (unsigned long long)e;
+        lg_publish(mine + 0, (unsigned)w, tag);
+        lg_publish(mine + 1, (unsigned)(w >> 32), tag);
+        lg_publish(mine + 2, (unsigned)(w >> 64), tag);
+        lg_publish(mine + 3, (unsigned)(w >> 96), tag);
+        lg_publish(mine + 4, (unsigned)e, tag);
+        lg_publish(mine + 5, (unsigned)(e >> 32), tag);   // the plain sum of a chunk is below 2^41
     }
-}
+    if (c != nchunks - 1) return;  // uniform over the workgroup
 
-template <bool BF16, bool VEC>
-__global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V, int nchunks, const void* __restrict__ zt,
-                                                             const void* __restrict__ zd, float inv_temp,
-                                                             const float* __restrict__ u,
-                                                             const float* __restrict__ rmax,
-                                                             const unsigned long long* __restrict__ rsum,
-                                                             const int32_t* __restrict__ accept_len,
-                                                             const u128* __restrict__ wsum,
-                                                             const unsigned long long* __restrict__ psum,
-                                                             int32_t* __restrict__ next_token,
-                                                             int32_t* __restrict__ priv_len) {
-    __shared__ u128 sh_w[kLgWaves];
-    __shared__ u128 sh_base;
-    __shared__ int sh_chunk;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const int n = accept_len[b];
-    if (priv_len && tid == 0) priv_len[b] -= k - n;  // the rejected drafts leave the branch's KV cache
+    // ---- the branch's last chunk collects: it waits only for workgroups dispatched before it ----
+    if (tid == 0) {
+        accept_len[b] = n;
+        if (priv_len) priv_len[b] -= k - n;  // the rejected drafts leave the branch's KV cache
+        sh_bad = 0;
+    }
+    __syncthreads();
+    for (int j = tid; j < nchunks; j += kLgThreads) {
+        unsigned long long* en = slots + ((size_t)b * nchunks + j) * 6;
+        unsigned long long v[6];
+        bool ok = false;
+        for (int spin = 0; spin < kLgSpinLimit; ++spin) {
+            ok = true;
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                v[i] = lg_peek(en + i);
+                ok = ok && (unsigned)(v[i] >> 32) == tag;
+            }
+            if (ok) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok) sh_bad = 1;  // never seen in practice: the producers were dispatched first and wait for nothing
+        sh_wsum[j] = (u128)(unsigned)v[0] | ((u128)(unsigned)v[1] << 32) | ((u128)(unsigned)v[2] << 64) | ((u128)(unsigned)v[3] << 96);
+        sh_psum[j] = (unsigned long long)(unsigned)v[4] | ((unsigned long long)(unsigned)v[5] << 32);
+#pragma unroll
+        for (int i = 0; i < 6; ++i)  // consumed: cleared, so that a captured launch (same tag) can be replayed
+            __hip_atomic_store(en + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
     // kLgMaxChunks = 2 * kLgThreads: every thread owns two consecutive chunk sums
     const int c0 = tid * 2;
     u128 w0 = 0, w1 = 0;
     unsigned long long p0 = 0, p1 = 0;
     if (c0 < nchunks) {
-        w0 = wsum[(size_t)b * nchunks + c0];
-        p0 = psum[(size_t)b * nchunks + c0];
+        w0 = sh_wsum[c0];
+        p0 = sh_psum[c0];
     }
     if (c0 + 1 < nchunks) {
-        w1 = wsum[(size_t)b * nchunks + c0 + 1];
-        p1 = psum[(size_t)b * nchunks + c0 + 1];
+        w1 = sh_wsum[c0 + 1];
+        p1 = sh_psum[c0 + 1];
     }
     u128 Z = block_sum_u128(w0 + w1, sh_w);
-    bool residual = n < k;
     if (residual && Z == 0) {  // empty residual: sample the target row itself (uniform branch: n and Z are)
         residual = false;
         w0 = p0;
         w1 = p1;
         Z = block_sum_u128(w0 + w1, sh_w);
     }
-    if (Z == 0) {  // a row without any weight (all logits -inf, or +inf / NaN among them): no token; uniform
+    if (Z == 0 || sh_bad) {  // a row without any weight (all logits -inf, or +inf / NaN among them): no token; uniform
         if (tid == 0) next_token[b] = -1;
         return;
     }
@@ -428,17 +464,12 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
         sh_base = second ? excl + w0 : excl;
     }
     __syncthreads();
-    const int c = sh_chunk;
+    const int cc = sh_chunk;
     const u128 base = sh_base;
-    const size_t es = BF16 ? 2 : 4;
-    const void* zt_row = static_cast<const char*>(zt) + (size_t)trow(b, n, k) * V * es;
-    const void* zd_row = residual ? static_cast<const char*>(zd) + ((size_t)b * k + n) * V * es : zt_row;
-    const RowStat sp = row_stat(rmax, rsum, trow(b, n, k));
-    const RowStat sq = residual ? row_stat(rmax, rsum, drow(B, b, n, k)) : sp;
-    u128 W[8];
-    unsigned long long Ep[8];
-    const int lo = c * kLgChunk + tid * 8;
-    lg_weights8<BF16, VEC>(zt_row, zd_row, lo, V, inv_temp, residual, sp, sq, W, Ep);
+    const void* zd_row2 = residual ? zd_row : zt_row;
+    const RowStat sq2 = residual ? sq : sp;
+    const int lo = cc * kLgChunk + tid * 8;
+    lg_weights8<BF16, VEC>(zt_row, zd_row2, lo, V, inv_temp, residual, sp, sq2, W, Ep);
     u128 local = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) local += W[i];
@@ -456,6 +487,8 @@ __global__ __launch_bounds__(kLgThreads) void lg_pick_kernel(int B, int k, int V
     }
 }
 
+static std::atomic<unsigned> g_lg_tag{0};
+
 struct LgLayout {
     size_t off_pmax, off_rmax, off_rsum, off_wsum, off_psum, total;
     int nchunks, npieces;
@@ -470,8 +503,8 @@ static inline LgLayout lg_layout(int B, int k, int V) {
     l.off_rmax = up(rows * l.npieces * sizeof(float));
     l.off_rsum = l.off_rmax + up(rows * sizeof(float));
     l.off_wsum = l.off_rsum + up(rows * sizeof(unsigned long long));
-    l.off_psum = l.off_wsum + up((size_t)B * l.nchunks * sizeof(u128));
-    l.total = l.off_psum + up((size_t)B * l.nchunks * sizeof(unsigned long long));
+    l.off_psum = l.off_wsum;  // one block of tagged words: 6 per (branch, chunk)
+    l.total = l.off_wsum + up((size_t)B * l.nchunks * 6 * sizeof(unsigned long long));
     return l;
 }
 static inline bool lg_sizes_ok(int B, int k, int V) {
@@ -490,7 +523,6 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
     float* rmax = reinterpret_cast<float*>(static_cast<char*>(workspace) + l.off_rmax);
     unsigned long long* rsum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_rsum);
     u128* wsum = reinterpret_cast<u128*>(static_cast<char*>(workspace) + l.off_wsum);
-    unsigned long long* psum = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + l.off_psum);
     const dim3 sgrid((unsigned)((long long)l.npieces * B * (2 * k + 1)));  // (piece, row) pairs, row-major
     LOTTS_LAUNCH((lg_max_kernel<BF16, VEC>), sgrid, dim3(kLgThreads), s, B, k, V, l.npieces, zt, zd, inv_temp, pmax,
                  rsum);
@@ -500,12 +532,11 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
                  rmax, rsum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    LOTTS_LAUNCH((lg_scan_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd,
-                       inv_temp, draft, u, rmax, rsum, accept_len, wsum, psum);
-    rc = check_launch();
-    if (rc != LOTTS_OK) return rc;
-    LOTTS_LAUNCH((lg_pick_kernel<BF16, VEC>), dim3(B), dim3(kLgThreads), s, B, k, V, l.nchunks, zt, zd, inv_temp, u,
-                       rmax, rsum, accept_len, wsum, psum, next_token, priv_len);
+    unsigned tag = g_lg_tag.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (tag == 0) tag = g_lg_tag.fetch_add(1, std::memory_order_relaxed) + 1;  // 0 is what cleared words hold
+    LOTTS_LAUNCH((lg_scan_pick_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), s, B, k, V, l.nchunks, tag, zt, zd,
+                 inv_temp, draft, u, rmax, rsum, accept_len, reinterpret_cast<unsigned long long*>(wsum), next_token,
+                 priv_len);
     return check_launch();
 }
 

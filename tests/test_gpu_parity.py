@@ -417,6 +417,11 @@ def test_confidence_vote(lotts, oracle, N, B, T):
     (64, 7168, 5120),       # 32B-shaped QKV projection for B * (k + 1) = 64 tokens (K split over workgroups)
     (64, 5120, 27648),      # 32B-shaped MLP down projection
     (36, 27648, 5120),      # 32B-shaped MLP up projection, M of the long-draft config
+    (64, 5120, 5120),       # 32B-shaped O projection
+    (33, 40, 2176),         # a second token tile of one row, weight rows past the end, an odd number of chunks
+    (64, 64, 32768),        # very long K on few rows: the deepest K split
+    (256, 55296, 5120),     # 32B-shaped gate+up projection at the largest token count (B = 64, k = 3)
+    (256, 5120, 27648),     # 32B-shaped down projection at the largest token count
 ])
 def test_skinny_gemm(lotts, oracle, M, N, K):
     print("gemm case", M, N, K, flush=True)
