@@ -173,6 +173,8 @@ def run_accept(lotts, oracle, s):
     S.CONFIGS["C2"].with_(B=3, V=262148, k=2),         # just beyond it: two launches
     S.CONFIGS["C2"].with_(B=5, V=16384 + 4, k=3),      # a last sub-chunk of one group of 4
     S.CONFIGS["C2"].with_(B=300, V=1024, k=1),         # many branches, one workgroup each
+    S.CONFIGS["C2"].with_(B=2000, V=8192, k=2),        # more workgroups than the chip holds at once: collectors wait for earlier ones
+    S.CONFIGS["C2"].with_(B=65535, V=256, k=1),        # the largest branch count
 ], ids=lambda c: "B%d_k%d_V%d" % (c.B, c.k, c.V))
 def test_accept_small(lotts, oracle, cfg):
     print("accept case", cfg, flush=True)
@@ -302,6 +304,7 @@ def logit_inputs(cfg, noise_std, salt=0, bf16=False):
     (S.CONFIGS["C3"], True, 1.0),                                  # full 32B-shaped size, bf16 logits
     (S.CONFIGS["C3"], False, 0.7),
     (S.CONFIGS["C4"].with_(B=64), True, 1.0),                      # the branch sweep's largest point, bf16 logits
+    (S.CONFIGS["C2"].with_(B=1500, V=4096, k=2), True, 1.0),       # more workgroups than the chip holds at once
 ], ids=lambda x: str(x) if not hasattr(x, "B") else "B%d_k%d_V%d" % (x.B, x.k, x.V))
 def test_accept_logits(lotts, oracle, cfg, bf16, inv_temp):
     print("accept-from-logits case", cfg, bf16, inv_temp, flush=True)
