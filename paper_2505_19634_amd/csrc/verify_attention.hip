@@ -516,10 +516,15 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             }
             l_run[t] = l_run[t] * alpha + psum;
             m_run[t] = m_new;
+            // Rescaling the accumulators is the largest block of vector work of a tile, and once a few hundred keys have
+            // gone by a tile rarely raises any row's maximum: alpha is exactly 1 for every lane then and the whole
+            // wavefront skips it (multiplying by 1 changes nothing, so the result is the same bit for bit).
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[t][db][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) oacc[t][db][i] *= alpha;
+            }
         }
         // O^T[d][query] += sum_key V[key][d] P^T[key][query]; V^T fragments by transposing LDS reads
 #pragma unroll
