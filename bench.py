@@ -251,6 +251,42 @@ def main() -> int:
     torch.cuda.synchronize()
     acc_ms = sum(e[1].elapsed_time(e[2]) for e in ev4) / K2
     vote_ms = sum(e[2].elapsed_time(e[3]) for e in ev4) / K2
+    # spec_accept back to back (the amortised figure of a launch-bound pass)
+    eb = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    eb[0].record(stream)
+    for i in range(64):
+        lib.spec_accept(*calls[i % nsets][1])
+    eb[1].record(stream)
+    torch.cuda.synchronize()
+    acc_ms_b2b = eb[0].elapsed_time(eb[1]) / 64
+
+    # the whole step replayed from a HIP graph (one graph holds one step per input set; the entry points only enqueue
+    # kernels, so they can be captured): what is left of the step when the host-side launch cost is gone
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        gsh = ctypes.c_void_p(int(side.cuda_stream))
+        gcalls = [tuple(a[:-1] + (gsh,) for a in c) for c in calls]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for c in gcalls:
+                rc = lib.verify_attention(*c[0]) | lib.spec_accept(*c[1]) | lib.majority_vote(*c[2])
+                if rc != 0:
+                    raise RuntimeError("capture failed")
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, min(K, 200) // nsets)
+        g0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / (reps * nsets)
+        del graph
+    except Exception as exc:  # a graph leg that fails must not take the bench line with it
+        graph_ms = "failed: %s" % exc
+
     # the amortised figure: one verify_attention call per decoder layer of the model the shape stands for,
     # launched back to back over the rotated inputs, between two event records
     n_layers = 64 if cfg.Hkv == 8 else 36
@@ -320,6 +356,7 @@ def main() -> int:
                                    cfg.name, cfg.B, cfg.k, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, cfg.L, cfg.V),
                    "input_sets_rotated": nsets},
         "ms_per_step_timer_off": ms_per_step_timer_off,
+        "ms_per_step_hip_graph_replay": graph_ms,
         "roofline": {"bound": "hbm",
                      "kernel": "attn_kernel (%s)" % ("all of verify_attention: one launch" if attn_launches == 1 else
                                                      "streams K and V; attn_merge_kernel follows"),
@@ -350,6 +387,7 @@ def main() -> int:
         "breakdown_ms": {"verify_attention": attn_ms_bracket, "spec_accept": acc_ms, "majority_vote": vote_ms},
         "spec_accept": {"algorithmic_bytes": bytes_acc, "GB/s": bytes_acc / (acc_ms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": bytes_acc / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "ms_back_to_back": acc_ms_b2b,
                         "mean_accepted": float(n0.mean()),
                         "acceptance_rate_sum_min_p_q": (None if cfg.k == 0 else
                                                         float(np.minimum(s0["p"][:, :cfg.k], s0["q"]).sum(-1).mean())),
