@@ -6,12 +6,14 @@
 //       re-derives the branch's accepted length n from the 2k gathered probabilities; each of its
 //       wavefronts turns one sub-chunk of the row to be sampled (residual max(0, p_n - q_n), or p_k)
 //       into 2^-40 fixed-point weights -- all of the sub-chunk's loads are requested before the first
-//       is used -- and publishes the sub-chunk's integer sums (residual and plain p) as four 8-byte
-//       words, each carrying half a sum and this call's 32-bit tag.  The workgroup of a branch's LAST
+//       is used -- and publishes the sub-chunk's integer sum as two 8-byte words, each carrying half
+//       of it and this call's 32-bit tag.  The workgroup of a branch's LAST
 //       slice then collects the branch's sums (it only ever waits for workgroups with smaller
 //       block indices, which were dispatched before it; the wait is bounded), locates the sub-chunk
 //       and the token where the integer CDF crosses T = floor(m * Z / 2^24), re-reading that one
-//       sub-chunk only, and clears the published words.  One read of the stop row(s) -- the only
+//       sub-chunk only, and clears the published words.  An empty residual (possible only after a
+//       draft of probability zero under both models) is resolved by that workgroup alone over the
+//       row p_n.  One read of the stop row(s) -- the only
 //       V-sized traffic -- and one launch: at these sizes the pass is bound by launch and memory
 //       latency, not by bandwidth.
 //   accept_scan_kernel + accept_pick_kernel  (V not a multiple of 4, unaligned rows, V > 2^18):

@@ -22,7 +22,8 @@
 //       (K read back row-wise as the MFMA A operand, V with the transposing LDS load), S^T = K Q^T
 //       and O^T += V^T P^T on 32x32x16 bf16 MFMA, flash-style running (max, sum, O).  The 4 states
 //       are combined through LDS after one barrier and the item's un-normalised partial goes to
-//       the workspace.  Arrivals are counted per (KV head, branch) with one device-scope atomic;
+//       the workspace.  Arrivals are counted per (KV head, branch) in a cell that carries the call's
+//       tag (what an earlier call left there, complete or not, counts as zero arrivals);
 //       the workgroup that delivers the last partial does the log-sum-exp merge of that branch's
 //       rows, normalises, converts and stores O (and LSE).  Partials cross workgroups -- and XCDs,
 //       each with its own L2 -- inside one launch, so they are written and read with 16-byte
@@ -33,6 +34,8 @@
 //       spread over the chip instead.
 // fp32 path: attn_f32_kernel, plain fp32 VALU arithmetic, one workgroup per output row; it
 // exists for exactness checks on small fp32 problems, not for speed.
+// Two entry points share all of this: verify_attention (the caller brings the workspace) and
+// verify_attention_noalloc (arrival cells and partials in a static device array of this file).
 #include <atomic>
 #include <cmath>
 
