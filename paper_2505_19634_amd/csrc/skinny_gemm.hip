@@ -9,8 +9,9 @@
 //       slab and read back as the MFMA A operand; the X chunk (up to 256 x 128) is fetched once per
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
-//   skinny_gemm_wide_kernel<MT, RT>  more than 64 tokens, or long K runs; grid (blocks of 128 * RT weight rows,
-//       K splits): RT row tiles per wavefront; with RT = 2 every X fragment read from LDS feeds two MFMAs.
+//   skinny_gemm_wide_kernel<MT, WAVES>  more than 64 tokens, or long K runs; grid (blocks of 256 weight rows,
+//       K splits): 4 wavefronts with two row tiles each (every X fragment read from LDS feeds two MFMAs),
+//       or, for 65..224 tokens, 8 wavefronts with one row tile each (two wavefronts per SIMD).
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -40,7 +41,7 @@ struct GemmParams {
 };
 
 struct GemmPlan {
-    int mt, wide, rt, nblocks, ksplit;
+    int mt, wide, rt, nblocks, ksplit;  // rt: row tiles per wavefront of the wide kernel (8 / wavefronts)
 };
 // K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
 // Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
@@ -61,15 +62,16 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     GemmPlan pl;
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
-    // The wide kernel with two row tiles per wavefront (64 weight rows, 256 per workgroup, one workgroup
-    // per unit) reuses every X fragment twice and halves the X traffic.  Up to 64 tokens it wins when its
-    // workgroups still get long runs of chunks (gate+up, down), and loses on short ones (QKV, O).  For
-    // 65..128 tokens the same loop with one row tile per wavefront fits two workgroups per unit (two
-    // wavefronts per SIMD hide each other's barrier and load waits) and measured 10 % faster; beyond 128
-    // tokens the accumulators leave room for one wavefront per SIMD only and the two-tile form is back.
-    pl.rt = (pl.mt == 3 || pl.mt == 4) ? 1 : 2;
-    const int nb_wide = (N + kGemmBlockN * pl.rt - 1) / (kGemmBlockN * pl.rt);
-    const int ks_wide = plan_ksplit(nb_wide, chunks, pl.rt == 1);
+    // The wide kernel covers 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged
+    // in LDS serves twice the rows of the narrow kernel.  It comes in two shapes.  Four wavefronts with two
+    // row tiles each (an X fragment read from LDS feeds two MFMAs): up to 64 tokens, where it wins when its
+    // workgroups still get long runs of chunks (gate+up, down) and loses on short ones (QKV, O), and at
+    // 225..256 tokens, where the accumulators leave room for one wavefront per SIMD only.  Eight wavefronts
+    // with one row tile each for 65..224 tokens: two wavefronts per SIMD hide each other's barrier and load
+    // waits, measured 4..22 % faster than the four-wavefront shape on the 32B-shaped layers.
+    pl.rt = (pl.mt >= 3 && pl.mt <= 7) ? 1 : 2;
+    const int nb_wide = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
+    const int ks_wide = plan_ksplit(nb_wide, chunks, false);
     pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
     if (pl.wide) {
         pl.nblocks = nb_wide;
@@ -197,21 +199,23 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
     }
 }
 
-// More than 64 tokens, and long K runs at any M.  Each wavefront owns RT MFMA row tiles of weight rows
-// (32 * RT) and all M tokens; with RT = 2 an X fragment read from LDS feeds two MFMAs and the workgroup's
-// X chunk serves 256 weight rows.  One W chunk (8 KB * RT per wavefront) is in flight while the previous
-// one is multiplied, as in the attention kernel; one X tile in LDS, rewritten behind a barrier once every
-// wavefront has finished with it.
-template <int MT, int RT>
-__global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_wide_kernel(const GemmParams p) {
+// More than 64 tokens, and long K runs at any M.  A workgroup of WAVES wavefronts covers 256 weight rows:
+// each wavefront owns RT = 8 / WAVES MFMA row tiles (32 * RT rows) and all M tokens; with RT = 2 an X
+// fragment read from LDS feeds two MFMAs.  One W chunk (8 KB * RT per wavefront) is in flight while the
+// previous one is multiplied, as in the attention kernel; one X tile in LDS, rewritten behind a barrier
+// once every wavefront has finished with it.
+template <int MT, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave, 1) void skinny_gemm_wide_kernel(const GemmParams p) {
+    constexpr int RT = 8 / WAVES;
+    constexpr int kThreads = WAVES * kWave;
     constexpr int WROWS = 32 * RT;
     constexpr int XROWS = 32 * MT;
-    constexpr int XPT = XROWS * 16 / kGemmThreads;  // 16-byte pieces of an X chunk per thread
+    constexpr int XPT = (XROWS * 16 + kThreads - 1) / kThreads;  // 16-byte pieces of an X chunk per thread
     __shared__ __attribute__((aligned(16))) unsigned char xbuf[XROWS * kGemmRowBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][WROWS * kGemmRowBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[WAVES][WROWS * kGemmRowBytes];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31, hh = lane >> 5;
-    const int n0 = blockIdx.x * (kGemmWaves * WROWS) + wave * WROWS;
+    const int n0 = blockIdx.x * (WAVES * WROWS) + wave * WROWS;
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
@@ -231,7 +235,7 @@ __global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_w
     auto fetch_x = [&](int c) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int idx = tid + i * kGemmThreads;
+            const int idx = tid + i * kThreads;
             int m = idx >> 4;
             m = m < p.M ? m : p.M - 1;
             xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
@@ -253,8 +257,9 @@ __global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_w
         __syncthreads();  // every wavefront has multiplied the previous chunk out of the X tile
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int idx = tid + i * kGemmThreads;
-            *reinterpret_cast<g_u32x4*>(xbuf + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
+            const int idx = tid + i * kThreads;
+            if (idx < XROWS * 16)  // the last piece of a thread may lie past the tile when 512 threads share it
+                *reinterpret_cast<g_u32x4*>(xbuf + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
         }
         __syncthreads();  // the X chunk is complete
 #pragma unroll
@@ -264,10 +269,10 @@ __global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_w
             fetch_x(c + 1);
             fetch_w(c + 1);
         }
-        // Y^T[n][m] += sum_k W[n][k] X[m][k]: two W fragments per k step, every X fragment feeds two MFMAs.
+        // Y^T[n][m] += sum_k W[n][k] X[m][k]: RT W fragments per k step, every X fragment feeds RT MFMAs.
         // The fragments of step s + 1 are requested before the MFMAs of step s are issued (the scheduling
         // barriers keep the compiler from sinking each read down to its use, where it would be waited for
-        // with nothing else in flight: one wavefront per SIMD has no neighbour to hide an LDS latency).
+        // with nothing else in flight: at most two wavefronts per SIMD are too few to hide an LDS latency).
         auto frags = [&](int s, g_bf16x8 (&a)[RT], g_bf16x8 (&b)[MT]) {
 #pragma unroll
             for (int r = 0; r < RT; ++r)
@@ -276,7 +281,9 @@ __global__ __launch_bounds__(kGemmThreads, (RT == 1 ? 2 : 1)) void skinny_gemm_w
             for (int t = 0; t < MT; ++t)
                 b[t] = *reinterpret_cast<const g_bf16x8*>(xbuf + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
         };
-        constexpr int NF = MT <= 7 ? 2 : 1;  // two fragment sets; one at 256 tokens, where registers run out
+        // Two fragment sets, or one where registers run out: at 256 tokens, and at 224 with two wavefronts
+        // per SIMD (256 registers each).
+        constexpr int NF = (MT <= 7 && !(WAVES == 8 && MT >= 7)) ? 2 : 1;
         g_bf16x8 fa[NF][RT], fb[NF][MT];
         if (NF == 2) frags(0, fa[0], fb[0]);
 #pragma unroll
@@ -373,17 +380,17 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit;
     p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads);
+    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads), wide8(8 * kWave);
     if (pl.wide) {
         switch (pl.mt) {
-            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 2>), grid, block, s, p); break;
-            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 2>), grid, block, s, p); break;
-            case 3: LOTTS_LAUNCH((skinny_gemm_wide_kernel<3, 1>), grid, block, s, p); break;
-            case 4: LOTTS_LAUNCH((skinny_gemm_wide_kernel<4, 1>), grid, block, s, p); break;
-            case 5: LOTTS_LAUNCH((skinny_gemm_wide_kernel<5, 2>), grid, block, s, p); break;
-            case 6: LOTTS_LAUNCH((skinny_gemm_wide_kernel<6, 2>), grid, block, s, p); break;
-            case 7: LOTTS_LAUNCH((skinny_gemm_wide_kernel<7, 2>), grid, block, s, p); break;
-            default: LOTTS_LAUNCH((skinny_gemm_wide_kernel<8, 2>), grid, block, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 4>), grid, block, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 4>), grid, block, s, p); break;
+            case 3: LOTTS_LAUNCH((skinny_gemm_wide_kernel<3, 8>), grid, wide8, s, p); break;
+            case 4: LOTTS_LAUNCH((skinny_gemm_wide_kernel<4, 8>), grid, wide8, s, p); break;
+            case 5: LOTTS_LAUNCH((skinny_gemm_wide_kernel<5, 8>), grid, wide8, s, p); break;
+            case 6: LOTTS_LAUNCH((skinny_gemm_wide_kernel<6, 8>), grid, wide8, s, p); break;
+            case 7: LOTTS_LAUNCH((skinny_gemm_wide_kernel<7, 8>), grid, wide8, s, p); break;
+            default: LOTTS_LAUNCH((skinny_gemm_wide_kernel<8, 4>), grid, block, s, p); break;
         }
     } else if (pl.mt == 1) {
         LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);

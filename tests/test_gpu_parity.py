@@ -425,6 +425,9 @@ def test_confidence_vote(lotts, oracle, N, B, T):
     (64, 64, 32768),        # very long K on few rows: the deepest K split
     (256, 55296, 5120),     # 32B-shaped gate+up projection at the largest token count (B = 64, k = 3)
     (256, 5120, 27648),     # 32B-shaped down projection at the largest token count
+    (224, 296, 896),        # seven token tiles on eight wavefronts, weight rows past the end, 7 chunks
+    (199, 1288, 1152),      # a ragged seventh token tile: X pieces past the tile are fetched and not staged
+    (160, 55296, 5120),     # 32B-shaped gate+up projection on the eight-wavefront form
 ])
 def test_skinny_gemm(lotts, oracle, M, N, K):
     print("gemm case", M, N, K, flush=True)
