@@ -4,6 +4,11 @@
 // identical answers ("vote").  One workgroup per question: the B rows of T scores are reduced
 // one after the other by all 256 threads (integer sums, so the order inside a row does not
 // matter), the selection runs over the B weights in LDS.  Latency-bound, like majority_vote.
+// Every floating-point operation in this file is rounded on its own, as the definition of the integer weights
+// says: the compiler's default for device code would otherwise be free to merge a multiplication and a
+// following addition or subtraction into one fused operation (one rounding), depending on how the
+// surrounding code happens to be shaped.  Fused multiply-adds are written out where the definition has them.
+#pragma clang fp contract(off)
 #include "lotts_common.h"
 
 namespace lotts {
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(kConfThreads) void confidence_vote_kernel(int B, in
             if (!first) continue;
             score = 0.f;
             for (int j = 0; j < B; ++j)
-                if (a[j] == a[i]) score = __fadd_rn(score, w[j]);  // branch order, one rounding per add
+                if (a[j] == a[i]) score = score + w[j];  // branch order, one rounding per add
         }
         const unsigned long long kk = ((unsigned long long)__float_as_uint(score) << 32) | (0xFFFFFFFFu - (unsigned)i);
         key = kk > key ? kk : key;

@@ -20,6 +20,11 @@
 //       grid (chunks, B) writes chunk sums; a second launch (B) picks.
 // All sums are 64-bit integers, so the result is independent of reduction order and equals a
 // sequential scan bit for bit.
+// Every floating-point operation in this file is rounded on its own, as the definition of the integer weights
+// says: the compiler's default for device code would otherwise be free to merge a multiplication and a
+// following addition or subtraction into one fused operation (one rounding), depending on how the
+// surrounding code happens to be shaped.  Fused multiply-adds are written out where the definition has them.
+#pragma clang fp contract(off)
 #include <atomic>
 
 #include "lotts_common.h"

@@ -22,6 +22,11 @@
 //                       branch's LAST chunk then collects the branch's sums (it waits only for workgroups with smaller
 //                       block indices, dispatched before it; the wait is bounded) and finds the chunk and the token
 //                       where the integer CDF crosses the threshold, re-reading that one chunk.
+// Every floating-point operation in this file is rounded on its own, as the definition of the integer weights
+// says: the compiler's default for device code would otherwise be free to merge a multiplication and a
+// following addition or subtraction into one fused operation (one rounding), depending on how the
+// surrounding code happens to be shaped.  Fused multiply-adds are written out where the definition has them.
+#pragma clang fp contract(off)
 #include <atomic>
 
 #include "lotts_common.h"
@@ -43,39 +48,48 @@ struct RowStat {
     unsigned long long S;  // sum of the integer weights
 };
 
+// One multiplication / subtraction, rounded to nearest.  Defined here, under the pragma above: the toolkit's
+// __fmul_rn / __fsub_rn are plain operators compiled under the default mode, and a product and a difference taken
+// through them were merged into one fused operation once the two were inlined next to each other.
+__device__ __forceinline__ float mul_rn(float a, float b) { return a * b; }
+__device__ __forceinline__ float sub_rn(float a, float b) { return a - b; }
+
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
 
-// 2^-f on [0, 1): the polynomial of the definition (c0 = 1 exactly), fused multiply-adds only
-__device__ __forceinline__ float pow2_neg_poly(float f) {
-    float g = 0x1.e243bep-14f;
-    g = __fmaf_rn(g, f, -0x1.52a284p-10f);
-    g = __fmaf_rn(g, f, 0x1.3a7ae4p-7f);
-    g = __fmaf_rn(g, f, -0x1.c6a66cp-5f);
-    g = __fmaf_rn(g, f, 0x1.ebfbaap-3f);
-    g = __fmaf_rn(g, f, -0x1.62e430p-1f);
-    g = __fmaf_rn(g, f, 1.0f);
+// 2^30 * 2^-f on [0, 1): the polynomial of the definition (c0 = 1 exactly), fused multiply-adds only, with every
+// coefficient scaled by 2^30.  Scaling by a power of two commutes with each rounding (no result comes near the
+// ends of the exponent range), so this is 2^30 times the definition's P(f), bit for bit.
+__device__ __forceinline__ float pow2_neg_poly_2p30(float f) {
+    float g = 0x1.e243bep+16f;
+    g = __fmaf_rn(g, f, -0x1.52a284p+20f);
+    g = __fmaf_rn(g, f, 0x1.3a7ae4p+23f);
+    g = __fmaf_rn(g, f, -0x1.c6a66cp+25f);
+    g = __fmaf_rn(g, f, 0x1.ebfbaap+27f);
+    g = __fmaf_rn(g, f, -0x1.62e430p+29f);
+    g = __fmaf_rn(g, f, 0x1p+30f);
     return g;
 }
 
 // E = trunc(2^t * 2^30) through the definition's steps; every operation individually rounded
-// (the weight is at most 2^30, so the conversion is a 32-bit one)
 __device__ __forceinline__ unsigned logit_weight(float y, float m) {
-    const float t = __fmul_rn(__fsub_rn(y, m), 0x1.715476p+0f);
+    const float t = mul_rn(sub_rn(y, m), 0x1.715476p+0f);
     // -t clamped to 31 (also for -inf logits and NaN from a row that is -inf throughout: fminf returns
     // the other operand): from 31 on the weight truncates to 0 by itself, P(0) * 2^-1 = 0.5, so the
     // definition's "0 when floor(-t) >= 31" needs no branch and no select
     const float a = fminf(-t, 31.0f);
-    const float nf = floorf(a);
-    const float f = __fsub_rn(a, nf);
-    const float g = pow2_neg_poly(f);
-    return __float2uint_rz(ldexpf(g, 30 - (int)nf));  // g * 2^(30 - n): exact scaling, then truncation
+    // a - floor(a) in one instruction (exact for 0 <= a <= 31, as the subtraction is); floor(a) by truncation
+    const float f = __builtin_amdgcn_fractf(a);
+    const unsigned n = (unsigned)(int)a;
+    // trunc(P * 2^(30 - n)) = trunc(P * 2^30) >> n: P * 2^30 <= 2^30 is a non-negative number, and flooring
+    // it before the division by 2^n does not change the floor of the quotient
+    return __float2uint_rz(pow2_neg_poly_2p30(f)) >> n;
 }
 
 template <bool BF16>
 __device__ __forceinline__ float load_y(const void* z, size_t idx, float inv_temp) {
     const float v = BF16 ? bf16_bits_to_float(static_cast<const unsigned short*>(z)[idx])
                          : static_cast<const float*>(z)[idx];
-    return __fmul_rn(v, inv_temp);
+    return mul_rn(v, inv_temp);
 }
 
 // 8 consecutive logits starting at a multiple of 8 (rows are 16-byte aligned when V % 8 == 0)
@@ -86,15 +100,15 @@ __device__ __forceinline__ void load_y8(const void* z, size_t idx, float inv_tem
         const unsigned w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            y[2 * i] = __fmul_rn(__uint_as_float(w[i] << 16), inv_temp);
-            y[2 * i + 1] = __fmul_rn(__uint_as_float(w[i] & 0xffff0000u), inv_temp);
+            y[2 * i] = mul_rn(__uint_as_float(w[i] << 16), inv_temp);
+            y[2 * i + 1] = mul_rn(__uint_as_float(w[i] & 0xffff0000u), inv_temp);
         }
     } else {
         const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + idx);
         const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(z) + idx + 4);
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) y[i] = __fmul_rn(v[i], inv_temp);
+        for (int i = 0; i < 8; ++i) y[i] = mul_rn(v[i], inv_temp);
     }
 }
 
@@ -119,8 +133,8 @@ __device__ __forceinline__ void load_piece(const void* z, size_t base, int lo, i
             const unsigned w[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                y[it][2 * e] = __fmul_rn(__uint_as_float(w[e] << 16), inv_temp);
-                y[it][2 * e + 1] = __fmul_rn(__uint_as_float(w[e] & 0xffff0000u), inv_temp);
+                y[it][2 * e] = mul_rn(__uint_as_float(w[e] << 16), inv_temp);
+                y[it][2 * e + 1] = mul_rn(__uint_as_float(w[e] & 0xffff0000u), inv_temp);
             }
         }
     } else {
@@ -139,7 +153,7 @@ __device__ __forceinline__ void load_piece(const void* z, size_t base, int lo, i
             const float v[8] = {raw[it][0].x, raw[it][0].y, raw[it][0].z, raw[it][0].w,
                                 raw[it][1].x, raw[it][1].y, raw[it][1].z, raw[it][1].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) y[it][e] = __fmul_rn(v[e], inv_temp);
+            for (int e = 0; e < 8; ++e) y[it][e] = mul_rn(v[e], inv_temp);
         }
     }
 }

@@ -305,6 +305,9 @@ def logit_inputs(cfg, noise_std, salt=0, bf16=False):
     (S.CONFIGS["C3"], False, 0.7),
     (S.CONFIGS["C4"].with_(B=64), True, 1.0),                      # the branch sweep's largest point, bf16 logits
     (S.CONFIGS["C2"].with_(B=1500, V=4096, k=2), True, 1.0),       # more workgroups than the chip holds at once
+    # many token decisions at a temperature other than 1
+    (S.CONFIGS["C1"].with_(B=600, V=999, k=2), False, 0.8),
+    (S.CONFIGS["C1"].with_(B=300, V=4096, k=2), True, 1.3),
 ], ids=lambda x: str(x) if not hasattr(x, "B") else "B%d_k%d_V%d" % (x.B, x.k, x.V))
 def test_accept_logits(lotts, oracle, cfg, bf16, inv_temp):
     print("accept-from-logits case", cfg, bf16, inv_temp, flush=True)
@@ -337,6 +340,83 @@ def test_accept_logits_degenerate(lotts, oracle):
     assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref)
     assert n_ref[0] == 2 and n_ref[1] == 0 and n_ref[2] == 1 and t_ref[2] == 100
     assert n_ref[4] == 1 and t_ref[4] == -1 and n_ref[5] == 2 and t_ref[5] == -1
+
+
+@pytest.mark.parametrize("bf16,inv_temp", [(False, 0.8), (True, 1.3), (True, 1.0)])
+def test_accept_logits_row_sums_are_the_definitions(lotts, oracle, bf16, inv_temp):
+    """White box: the integer weight sum S and the maximum of every row, as the launches leave them in the
+    workspace, against the oracle's bit for bit.  The outputs alone hardly see a weight that is off by one (a
+    token changes only if the threshold falls into that sliver of the CDF), and that is what a scaling and a
+    subtraction merged into one fused operation -- one rounding instead of the definition's two -- produces."""
+    cfg = S.CONFIGS["C1"].with_(B=5, V=40000, k=2)
+    zt, zd, draft, u = logit_inputs(cfg, 1.0, salt=77, bf16=bf16)
+    rows = cfg.B * (2 * cfg.k + 1)
+    up = lambda x: (x + 255) & ~255
+    npieces = (cfg.V + 16383) // 16384
+    off_rmax = up(rows * npieces * 4)                      # piece maxima come first
+    off_rsum = off_rmax + up(rows * 4)
+    ws = torch.zeros((lotts.load().spec_accept_logits_workspace_bytes(cfg.B, cfg.k, cfg.V),), dtype=torch.uint8, device=DEV)
+    lotts.spec_accept_logits(to_dev(zt, bf16), to_dev(zd, bf16), to_dev(draft), to_dev(u), inv_temperature=inv_temp,
+                             workspace=ws)
+    torch.cuda.synchronize()
+    rmax = ws[off_rmax:off_rmax + rows * 4].view(torch.float32).cpu().numpy()
+    rsum = ws[off_rsum:off_rsum + rows * 8].view(torch.int64).cpu().numpy()
+    all_rows = [zt[b, j] for b in range(cfg.B) for j in range(cfg.k + 1)] + \
+               [zd[b, j] for b in range(cfg.B) for j in range(cfg.k)]
+    for r, z in enumerate(all_rows):
+        E, S_ref = oracle.logit_weights(z, inv_temp)
+        zf = S.bf16_bits_to_f32(z) if bf16 else z
+        assert int(rsum[r]) == S_ref, (r, int(rsum[r]), S_ref)
+        assert rmax[r] == (zf.astype(np.float32) * np.float32(inv_temp)).max(), r
+
+
+def test_accept_logits_with_a_workspace_full_of_garbage(lotts, oracle):
+    """Every word the workgroups of the one launch hand to each other carries the call's tag: random bytes, or
+    the words of earlier calls on other sizes, are not taken for this call's."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(12)
+    ws = torch.randint(0, 256, (8 << 20,), dtype=torch.uint8, device=DEV, generator=g)
+    for cfg in (S.CONFIGS["C2"].with_(B=6, V=40000, k=3), S.CONFIGS["C2"].with_(B=9, V=20000, k=2),
+                S.CONFIGS["C2"].with_(B=6, V=40000, k=3)):
+        print("garbage workspace, logits", cfg, flush=True)
+        zt, zd, draft, u = logit_inputs(cfg, 1.0, salt=cfg.B, bf16=True)
+        n_ref, t_ref = oracle.spec_accept_logits(zt, zd, draft, u)
+        for _ in range(2):
+            n, t = lotts.spec_accept_logits(to_dev(zt, True), to_dev(zd, True), to_dev(draft), to_dev(u), workspace=ws)
+            assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref)
+
+
+def test_accept_logits_can_be_captured_and_replayed_on_new_logits(lotts, oracle):
+    """A captured launch keeps its tag, so the launch itself clears every word it exchanged: replays on new
+    logits in the same buffers must equal eager calls, with eager calls on the same workspace in between."""
+    cfg = S.CONFIGS["C2"].with_(B=8, V=50000, k=3)
+    sets = [logit_inputs(cfg, 1.0, salt=40 + i, bf16=True) for i in range(3)]
+    refs = [oracle.spec_accept_logits(*x) for x in sets]
+    zt, zd = to_dev(sets[0][0], True), to_dev(sets[0][1], True)
+    draft, u = to_dev(sets[0][2]), to_dev(sets[0][3])
+    n = torch.empty((cfg.B,), dtype=torch.int32, device=DEV)
+    t = torch.empty((cfg.B,), dtype=torch.int32, device=DEV)
+    ws = torch.zeros((lotts.load().spec_accept_logits_workspace_bytes(cfg.B, cfg.k, cfg.V),), dtype=torch.uint8, device=DEV)
+    call = lambda stream=None: lotts.spec_accept_logits(zt, zd, draft, u, accept_len=n, next_token=t, workspace=ws,
+                                                        stream=stream)
+    call()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream())
+    for rep in range(6):
+        i = rep % 3
+        zt.copy_(to_dev(sets[i][0], True)); zd.copy_(to_dev(sets[i][1], True))
+        draft.copy_(to_dev(sets[i][2])); u.copy_(to_dev(sets[i][3]))
+        if rep % 2:                                        # an eager call (new tag) on the same workspace in between
+            call()
+        n.fill_(-7); t.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(n.cpu().numpy(), refs[i][0]) and np.array_equal(t.cpu().numpy(), refs[i][1]), rep
 
 
 def test_accept_logits_against_the_probability_oracle(lotts, oracle):
