@@ -10,9 +10,12 @@
  *   - Return value: LOTTS_OK or a negative lotts_status.  All argument checks run on the
  *     host before anything is launched; a failed call launches nothing.
  *   - Scratch memory is passed in as `workspace`; the *_workspace_bytes queries say how much.
- *     Calls that share a workspace must be ordered on one stream.  spec_accept takes any
- *     contents.  verify_attention keeps arrival cells in the first 128 KiB of its workspace:
- *     the buffer must be ZERO-FILLED ONCE before its first use (hipMemset or a fill kernel).
+ *     Calls that share a workspace must be ordered on one stream.  spec_accept and
+ *     spec_accept_logits take any contents, each other's leftovers included (what their kernels
+ *     exchange carries a tag that no other call of the process has).  A buffer given to
+ *     verify_attention stays verify_attention's: it keeps arrival cells in the first 128 KiB,
+ *     the buffer must be ZERO-FILLED ONCE before its first use (hipMemset or a fill kernel),
+ *     and again if another entry point has written to it in between.
  *     After that it serves any number of calls of any geometry without clearing: every cell
  *     carries the tag of the call that wrote it (tags grow from call to call within the
  *     process), a call treats whatever an earlier call left there as zero arrivals, and a

@@ -2,6 +2,7 @@
 // profiler.  Between lotts_timer_start and lotts_timer_stop every launch made by the calling host
 // thread carries a pair of events of its own (hipExtLaunchKernel attaches them to the dispatch), so
 // each pair reads that kernel's start and end on the device: no gap between commands is included.
+#include <atomic>
 #include <vector>
 
 #include "lotts_common.h"
@@ -15,6 +16,13 @@ struct KernelTimer {
     bool paused = false;
 };
 static thread_local KernelTimer g_timer;
+
+static std::atomic<unsigned> g_word_tag{0};
+unsigned next_word_tag() {
+    unsigned tag = g_word_tag.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (tag == 0) tag = g_word_tag.fetch_add(1, std::memory_order_relaxed) + 1;  // 0 is what cleared words hold
+    return tag;
+}
 
 bool timer_take(hipEvent_t* start, hipEvent_t* stop) {
     KernelTimer& t = g_timer;

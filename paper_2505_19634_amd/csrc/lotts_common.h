@@ -19,6 +19,11 @@ constexpr int kNumXCD = 8;
 // the pair reads that kernel's own start and end on the device.
 bool timer_take(hipEvent_t* start, hipEvent_t* stop);
 
+// Tag of a call whose workgroups exchange tagged words through the workspace (spec_accept,
+// spec_accept_logits): never 0, and different for every such call of the process whichever entry point
+// makes it, so one buffer can serve both without either taking the other's leftovers for its own.
+unsigned next_word_tag();
+
 // Every launch of the library goes through here: no dynamic LDS, the caller's stream.
 #define LOTTS_LAUNCH(kernel, grid, block, stream, ...)                                                        \
     do {                                                                                                      \

@@ -25,8 +25,6 @@
 // following addition or subtraction into one fused operation (one rounding), depending on how the
 // surrounding code happens to be shaped.  Fused multiply-adds are written out where the definition has them.
 #pragma clang fp contract(off)
-#include <atomic>
-
 #include "lotts_common.h"
 
 namespace lotts {
@@ -528,7 +526,6 @@ __global__ __launch_bounds__(kAccThreads) void accept_fused_kernel(int B, int k,
     }
 }
 
-static std::atomic<unsigned> g_accept_tag{0};
 
 }  // namespace lotts
 
@@ -556,8 +553,7 @@ extern "C" int spec_accept(int32_t B, int32_t k, int32_t V, const float* p, cons
     const bool vec = (V % 4 == 0) && (((uintptr_t)p & 15) == 0) && (k == 0 || ((uintptr_t)q & 15) == 0);
     if (vec && V <= kFuMaxV) {  // one launch
         const FusedPlan fp = plan_fused(V);
-        unsigned tag = g_accept_tag.fetch_add(1, std::memory_order_relaxed) + 1;
-        if (tag == 0) tag = g_accept_tag.fetch_add(1, std::memory_order_relaxed) + 1;  // 0 is what cleared words hold
+        const unsigned tag = next_word_tag();
         const dim3 fgrid((unsigned)((long long)B * fp.S));
         if (fp.iters <= 4)
             LOTTS_LAUNCH(accept_fused_kernel<4>, fgrid, dim3(kAccThreads), s, B, k, V, fp, tag, p, q, draft, u, accept_len,

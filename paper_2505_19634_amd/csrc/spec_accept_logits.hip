@@ -27,8 +27,6 @@
 // following addition or subtraction into one fused operation (one rounding), depending on how the
 // surrounding code happens to be shaped.  Fused multiply-adds are written out where the definition has them.
 #pragma clang fp contract(off)
-#include <atomic>
-
 #include "lotts_common.h"
 
 namespace lotts {
@@ -501,7 +499,6 @@ __global__ __launch_bounds__(kLgThreads) void lg_scan_pick_kernel(int B, int k, 
     }
 }
 
-static std::atomic<unsigned> g_lg_tag{0};
 
 struct LgLayout {
     size_t off_pmax, off_rmax, off_rsum, off_wsum, off_psum, total;
@@ -546,8 +543,7 @@ static int lg_launch(int B, int k, int V, const void* zt, const void* zd, float 
                  rmax, rsum);
     rc = check_launch();
     if (rc != LOTTS_OK) return rc;
-    unsigned tag = g_lg_tag.fetch_add(1, std::memory_order_relaxed) + 1;
-    if (tag == 0) tag = g_lg_tag.fetch_add(1, std::memory_order_relaxed) + 1;  // 0 is what cleared words hold
+    const unsigned tag = next_word_tag();
     LOTTS_LAUNCH((lg_scan_pick_kernel<BF16, VEC>), dim3(l.nchunks, B), dim3(kLgThreads), s, B, k, V, l.nchunks, tag, zt, zd,
                  inv_temp, draft, u, rmax, rsum, accept_len, reinterpret_cast<unsigned long long*>(wsum), next_token,
                  priv_len);

@@ -386,6 +386,24 @@ def test_accept_logits_with_a_workspace_full_of_garbage(lotts, oracle):
             assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref)
 
 
+def test_accept_and_accept_logits_can_share_one_workspace(lotts, oracle):
+    """Both exchange tagged words through the workspace; the tags come from one counter, so calls of the two
+    entry points that alternate on one buffer never take each other's leftovers for their own."""
+    cfg = S.CONFIGS["C2"].with_(B=8, V=50000, k=3)
+    s = S.accept_inputs(cfg)
+    d = [to_dev(s[x]) for x in ("p", "q", "draft", "u")]
+    n_ref, t_ref = oracle.spec_accept(s["p"], s["q"], s["draft"], s["u"])
+    zt, zd, draft, u = logit_inputs(cfg, 1.0, salt=5, bf16=True)
+    z = [to_dev(zt, True), to_dev(zd, True), to_dev(draft), to_dev(u)]
+    ln_ref, lt_ref = oracle.spec_accept_logits(zt, zd, draft, u)
+    ws = torch.zeros((8 << 20,), dtype=torch.uint8, device=DEV)
+    for _ in range(4):
+        n, t = lotts.spec_accept(*d, workspace=ws)
+        ln, lt = lotts.spec_accept_logits(*z, workspace=ws)
+        assert np.array_equal(n.cpu().numpy(), n_ref) and np.array_equal(t.cpu().numpy(), t_ref)
+        assert np.array_equal(ln.cpu().numpy(), ln_ref) and np.array_equal(lt.cpu().numpy(), lt_ref)
+
+
 def test_accept_logits_can_be_captured_and_replayed_on_new_logits(lotts, oracle):
     """A captured launch keeps its tag, so the launch itself clears every word it exchanged: replays on new
     logits in the same buffers must equal eager calls, with eager calls on the same workspace in between."""
