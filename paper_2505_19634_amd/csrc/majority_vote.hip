@@ -55,34 +55,32 @@ __global__ __launch_bounds__(kVoteThreads) void majority_vote_kernel(int B, cons
     }
 }
 
-// Up to 64 answers (the paper's branch counts): one wavefront, one answer per lane, no LDS and no
-// barrier -- the whole kernel is one load, B shuffles and one store.
+// Up to 64 answers (the paper's branch counts): one wavefront, one answer per lane, no LDS, no barrier and
+// no cross-lane data movement beyond reading one lane at a time: for every lane j in turn the wavefront
+// compares its answers with answer j in one instruction, and the resulting lane mask -- a scalar -- gives the
+// id's vote count (its population count) and tells whether j is the id's first occurrence (its lowest set bit).
+// The whole kernel is one load, B compares with scalar bookkeeping, and one store.
 __global__ __launch_bounds__(kWave) void majority_vote_wave_kernel(int B, const int32_t* __restrict__ answers,
                                                                    int32_t* __restrict__ winner,
                                                                    int32_t* __restrict__ winner_count) {
     const int n = blockIdx.x, lane = threadIdx.x;
     const int32_t ai = lane < B ? answers[(size_t)n * B + lane] : -1;
-    int votes = 0;
-    bool first = true;
-    for (int j = 0; j < B; ++j) {
-        const int32_t aj = __shfl(ai, j, kWave);
-        const bool same = (aj == ai);
-        votes += same;
-        first = first && !(same && j < lane);
+    int best = 0;
+    int32_t best_a = -1;
+    for (int j = 0; j < B; ++j) {  // everything in this loop is uniform over the wavefront
+        const int32_t aj = __builtin_amdgcn_readlane(ai, j);
+        if (aj < 0) continue;  // "no answer" does not compete
+        const unsigned long long same = __ballot(ai == aj);
+        if (__ffsll((long long)same) - 1 != j) continue;  // a later occurrence: the id has competed already
+        const int votes = __popcll(same);
+        if (votes > best) {  // strictly more: of equal counts the earlier first occurrence stays
+            best = votes;
+            best_a = aj;
+        }
     }
-    unsigned long long key = 0;  // same key as the general kernel
-    if (ai >= 0 && first) key = ((unsigned long long)votes << 32) | (0xFFFFFFFFu - (unsigned)lane);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const unsigned long long o = shfl_down_u64(key, d);
-        key = o > key ? o : key;
-    }
-    key = shfl_u64(key, 0);
-    const int wl = (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFu));
-    const int32_t wa = __shfl(ai, key ? wl : 0, kWave);
     if (lane == 0) {
-        winner[n] = key ? wa : -1;
-        winner_count[n] = (int32_t)(key >> 32);
+        winner[n] = best_a;
+        winner_count[n] = best;
     }
 }
 
