@@ -526,6 +526,8 @@ def test_confidence_vote(lotts, oracle, N, B, T):
     (224, 296, 896),        # seven token tiles on eight wavefronts, weight rows past the end, 7 chunks
     (199, 1288, 1152),      # a ragged seventh token tile: X pieces past the tile are fetched and not staged
     (160, 55296, 5120),     # 32B-shaped gate+up projection on the eight-wavefront form
+    (199, 27656, 5120),     # X through global-to-LDS stages: a ragged seventh token tile, 8 weight rows in the last block, K split in two
+    (130, 55432, 4224),     # the same kernel with five token tiles, 33 chunks per workgroup, no K split
 ])
 def test_skinny_gemm(lotts, oracle, M, N, K):
     print("gemm case", M, N, K, flush=True)
