@@ -449,11 +449,9 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_wide8_kernel(const G
         fetch_w(c_lo);
     }
     // The waits before the barriers are written out: a wavefront's global-to-LDS loads count in vmcnt like its
-    // other loads, in issue order, and a stage must have landed before the barrier that publishes it.  The last
-    // chunk requests itself once more where earlier ones request their successor (16 KB per wavefront that nobody
-    // reads), so that the number of loads in flight at each barrier is the same in every iteration.
+    // other loads, in issue order, and a stage must have landed before the barrier that publishes it.
     for (int c = c_lo; c < c_hi; ++c) {
-        const int nxt = c + 1 < c_hi ? c + 1 : c;
+        const bool more = c + 1 < c_hi;  // uniform
         // first half of chunk c: its X stage and W chunk c have been requested and nothing else is in flight
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // everybody's part of xs0 has landed; xs1 is free
 #pragma unroll
@@ -461,15 +459,17 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_wide8_kernel(const G
             *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
         fetch_x(c, 1, xs1);
         __builtin_amdgcn_sched_barrier(0);  // the wait below counts on this order: the stage's loads, then the 8 of W
-        fetch_w(nxt);
+        if (more) fetch_w(c + 1);
         __builtin_amdgcn_sched_barrier(0);
         multiply(0, xs0);
-        // second half: the stage requested above; the 8 W loads issued after it stay in flight
-        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // xs1 has landed; xs0 is free
-        fetch_x(nxt, 0, xs0);
+        // second half: the stage requested above has landed; the 8 W loads issued after it, if any, stay in flight
+        if (more)
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // xs1 has landed; xs0 is free
+        else
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (more) fetch_x(c + 1, 0, xs0);
         multiply(1, xs1);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the loads of the last iteration that nobody uses
     // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
