@@ -544,9 +544,10 @@ def test_skinny_gemm(lotts, oracle, M, N, K):
     assert np.linalg.norm(y - ref) / np.linalg.norm(ref) <= 3e-3
 
 
-def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle):
-    g = S.rng_for(7, 31)
-    M, N, K = 48, 640, 768
+@pytest.mark.parametrize("M", [48, 256])    # 256 tokens take the kernel that brings X in by global-to-LDS loads
+def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle, M):
+    g = S.rng_for(7, 31, salt=M)
+    N, K = 640, 768
     Xf = torch.from_numpy(S.f32_to_bf16_bits(g.standard_normal((M, K + 64), dtype=np.float32))).to(DEV).view(torch.bfloat16)
     Wf = torch.from_numpy(S.f32_to_bf16_bits(g.standard_normal((N, K + 8), dtype=np.float32) * 0.03)).to(DEV).view(torch.bfloat16)
     X, W = Xf[:, :K], Wf[:, :K]
