@@ -4,7 +4,9 @@
 // one parallel forward; Section 3.1: the step is bound by loading the KV cache).
 //
 // bf16 path (MFMA, gfx950), normally ONE launch:
-//   attn_kernel           one launch over "work items", one 4-wavefront workgroup each.  An item
+//   attn_kernel           one launch over "work items", one workgroup each: 4 wavefronts for up to 32
+//       query rows, 8 for up to 64 (two groups of 4, one row tile each; wavefront w of either group
+//       streams the same key tiles, so the two load half a tile each into a slab both read).  An item
 //       is a share of the keys of one KV segment and a stack of up to 32*NQT query rows that all
 //       read those keys:
 //         - private item: the G*R rows (G = Hq/Hkv query heads x R = k+1 positions) of one branch
@@ -305,8 +307,13 @@ struct KeyRun {
 // ---------------------------------------------------------------------------------------------
 // bf16 partial attention
 // ---------------------------------------------------------------------------------------------
-template <int D, int NQT>
-__global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(const AttnParams prm) {
+template <int D, int NQT, int GROUPS>
+__global__ __launch_bounds__(kAttnThreads * GROUPS, (NQT > 1 ? 1 : 2)) void attn_kernel(const AttnParams prm) {
+    // GROUPS = 2: eight wavefronts, two per SIMD.  The second group of four takes the second row tile; wavefront w of
+    // either group streams the same key tiles, so the two share them: each loads half of a tile into a slab both
+    // read (two slabs per pair, taking turns; one workgroup barrier per tile).
+    static_assert(GROUPS == 1 || (GROUPS == 2 && NQT == 2), "two groups split two row tiles");
+    constexpr int TW = NQT / GROUPS;       // row tiles per wavefront
     constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide blocks of the head dimension
     constexpr int KSTRIDE = D * 2 + 16;    // bytes per key row of the K slab (pad: conflict-free 16-byte row reads)
@@ -316,11 +323,14 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     constexpr int OSTRIDE = D + 4;         // floats per row of a wavefront's merge buffer
     constexpr int OBUF = kRowTile * OSTRIDE * 4;
     static_assert(OBUF <= SLAB, "the merge buffer reuses the wavefront's slab");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kAttnWaves * SLAB];
-    __shared__ float sh_m[kAttnWaves][kRowTile];
-    __shared__ float sh_l[kAttnWaves][kRowTile];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kAttnWaves * GROUPS * SLAB];
+    __shared__ float sh_m[kAttnWaves * GROUPS][kRowTile];
+    __shared__ float sh_l[kAttnWaves * GROUPS][kRowTile];
+    __shared__ int sh_nt[kAttnWaves * GROUPS];
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int tid = threadIdx.x, wave_all = tid / kWave, lane = tid & (kWave - 1);
+    const int grp = GROUPS == 1 ? 0 : wave_all / kAttnWaves;         // which row tile(s) this wavefront works on
+    const int wave = GROUPS == 1 ? wave_all : wave_all % kAttnWaves;  // which of the item's four runs of key tiles it streams
     const int ln = lane & 31;   // MFMA column (query row) / A row (key or d) owned by this lane
     const int hh = lane >> 5;   // which half of each 16-wide k block this lane holds
     const AttnPlan& pl = prm.plan;
@@ -373,7 +383,7 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     }
     const int n_fold = run[0].ntiles;
 
-    unsigned char* kslab = lds + wave * SLAB;
+    unsigned char* kslab = lds + wave * SLAB;  // GROUPS = 2: re-pointed every tile
     unsigned char* vslab = kslab + KSLAB;
     // Tile staging: every load instruction of the wavefront covers RPI whole key rows (16 bytes per
     // lane, consecutive lanes consecutive addresses), the same pattern for K and V.
@@ -387,13 +397,14 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
 
     // The next tile is fetched into registers while the current one is being consumed from LDS.
     // K and V are read exactly once, so the loads carry the non-temporal hint.
-    u32x4 kst[NVL], vst[NVL];
+    constexpr int NLD = NVL / GROUPS;      // load instructions per tile and operand issued by this wavefront
+    u32x4 kst[NLD], vst[NLD];
     auto fetch = [&](int it) {
         const KeyRun& r = run[it < n_fold ? 0 : 1];
         const int kb_ = r.lo + (it < n_fold ? it : it - n_fold) * r.step;
 #pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-            int key = kb_ + i * RPI + v_row;
+        for (int i = 0; i < NLD; ++i) {
+            int key = kb_ + (i * GROUPS + grp) * RPI + v_row;
             key = key < r.hi ? key : r.hi - 1;  // a ragged last tile re-reads its last row; masked below
             const long long off = (long long)key * r.stride_t + v_chunk * 8;
             kst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(r.K + off));
@@ -403,11 +414,11 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     if (n_fold > 0) fetch(0);
 
     // ---- Q fragments (B operand of S^T = K Q^T: lane = query row ln, 8 contiguous d) ----
-    bf16x8 qf[NQT][KS];
-    int q_r[NQT];  // position (0..k) of this lane's query row
+    bf16x8 qf[TW][KS];
+    int q_r[TW];  // position (0..k) of this lane's query row
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) {
-        const int rho = rho0 + t * kRowTile + ln;
+    for (int t = 0; t < TW; ++t) {
+        const int rho = rho0 + (grp * TW + t) * kRowTile + ln;
         const bool valid = rho < rho_end;
         const int rc = valid ? rho : rho0;
         const int b = rc / GR, rl = rc - b * GR;
@@ -453,15 +464,15 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     run[1].ntiles = run[1].lo < seg_len ? (seg_len - run[1].lo + run[1].step - 1) / run[1].step : 0;
     const int n_tiles = n_fold + run[1].ntiles;
     if (n_fold == 0 && n_tiles > 0) fetch(0);
-    int lim[NQT];  // keys of this wavefront's own run visible to this lane's query row
+    int lim[TW];  // keys of this wavefront's own run visible to this lane's query row
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) lim[t] = min(is_private ? causal_base + q_r[t] : causal_base, run[1].hi);
+    for (int t = 0; t < TW; ++t) lim[t] = min(is_private ? causal_base + q_r[t] : causal_base, run[1].hi);
 
     // ---- running state ----
-    f32x16 oacc[NQT][DB];
-    float m_run[NQT], l_run[NQT];
+    f32x16 oacc[TW][DB];
+    float m_run[TW], l_run[TW];
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) {
+    for (int t = 0; t < TW; ++t) {
         m_run[t] = -INFINITY;
         l_run[t] = 0.f;
 #pragma unroll
@@ -470,24 +481,42 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
-    for (int it = 0; it < n_tiles; ++it) {
+    int n_loop = n_tiles;
+    if (GROUPS > 1) {  // the barrier of the tile loop needs the same trip count in every wavefront: the longest run's
+        if (lane == 0) sh_nt[wave_all] = n_tiles;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kAttnWaves * GROUPS; ++w) n_loop = max(n_loop, sh_nt[w]);
+    }
+    for (int it = 0; it < n_loop; ++it) {
+        const bool live = GROUPS == 1 || it < n_tiles;  // uniform over the wavefront
         const bool folded = it < n_fold;
         const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * run[1].step;
-#pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-            *reinterpret_cast<u32x4*>(kslab + (i * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
-            *reinterpret_cast<u32x4*>(vslab + (i * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
+        if (GROUPS > 1) {
+            kslab = lds + ((it & 1) * kAttnWaves + wave) * SLAB;
+            vslab = kslab + KSLAB;
         }
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                *reinterpret_cast<u32x4*>(kslab + ((i * GROUPS + grp) * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
+                *reinterpret_cast<u32x4*>(vslab + ((i * GROUPS + grp) * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
+            }
+        }
+        // Both halves of the tile are in the slab; the other slab of the pair, which the next tile will overwrite, is
+        // free: whoever passes this barrier has left the tile before this one behind.
+        if (GROUPS > 1) __syncthreads();
         if (it + 1 < n_tiles) fetch(it + 1);
+        if (!live) continue;
         // K fragments (A operand of S^T = K Q^T: lane = key row ln, 8 contiguous d)
         bf16x8 kf[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             kf[s] = *reinterpret_cast<const bf16x8*>(kslab + ln * KSTRIDE + (2 * s + hh) * 16);
 
-        bf16x8 pf[NQT][2];
+        bf16x8 pf[TW][2];
 #pragma unroll
-        for (int t = 0; t < NQT; ++t) {
+        for (int t = 0; t < TW; ++t) {
             // S^T[key][query] = sum_d K[key][d] Q[query][d]
             f32x16 acc;
 #pragma unroll
@@ -546,7 +575,7 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
                 vf.s[0] = lo;
                 vf.s[1] = hi;
 #pragma unroll
-                for (int t = 0; t < NQT; ++t)
+                for (int t = 0; t < TW; ++t)
                     oacc[t][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[t][kb], oacc[t][db], 0, 0, 0);
             }
         }
@@ -560,20 +589,23 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     constexpr int F4 = D / 4;
     constexpr int QPT = kRowTile * F4 / kAttnThreads;  // 4 (D = 128) or 2 (D = 64)
     constexpr int RSTEP = kAttnThreads / F4;
-    float* obuf = reinterpret_cast<float*>(lds + wave * SLAB);
+    if (GROUPS > 1) __syncthreads();  // nobody reads a key tile any more: the slabs become merge buffers
+    float* obuf = reinterpret_cast<float*>(lds + wave_all * SLAB);
     const __amdgpu_buffer_rsrc_t rs = ws_rsrc(prm);
-    const int c4 = tid % F4, row0 = tid / F4;
+    const int tig = tid % kAttnThreads;  // thread within its group of four wavefronts
+    const int c4 = tig % F4, row0 = tig / F4;
     float4 own_o[QPT];    // the last row tile's combined quads, kept for a merge by this workgroup
     float2 own_ml[QPT];
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) {
+    for (int t = 0; t < TW; ++t) {
         if (t > 0) __syncthreads();  // the previous row tile has been read out
+        const int tile = grp * TW + t;  // row tile of the item
         const float lsum = l_run[t] + shfl_xor_f(l_run[t], 32);
         if (hh == 0) {
-            sh_m[wave][ln] = m_run[t];
-            sh_l[wave][ln] = lsum;
+            sh_m[wave_all][ln] = m_run[t];
+            sh_l[wave_all][ln] = lsum;
         }
-        const int nrows = min(kRowTile, rho_end - (rho0 + t * kRowTile));
+        const int nrows = min(kRowTile, rho_end - (rho0 + tile * kRowTile));
         if (ln < nrows) {  // rows beyond the item's are never read back
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -592,9 +624,9 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             for (int w = 0; w < kAttnWaves; ++w) {
                 if (q * RSTEP >= nrows) continue;  // a whole group of rows beyond the item's (uniform)
                 const int row = min(row0 + q * RSTEP, nrows - 1);
-                mw[q][w] = sh_m[w][row];
-                lw[q][w] = sh_l[w][row];
-                ov[q][w] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(lds + w * SLAB) +
+                mw[q][w] = sh_m[grp * kAttnWaves + w][row];
+                lw[q][w] = sh_l[grp * kAttnWaves + w][row];
+                ov[q][w] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(lds + (grp * kAttnWaves + w) * SLAB) +
                                                             row * OSTRIDE + c4 * 4);
             }
 #pragma unroll
@@ -619,7 +651,7 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
             own_o[q] = o;
             own_ml[q] = make_float2(mg, lg);
             if (row < nrows) {
-                const unsigned rho = rho0 + t * kRowTile + row;
+                const unsigned rho = rho0 + tile * kRowTile + row;
                 const unsigned pidx = ((unsigned)kvh * prm.B * GR + rho) * pl.nslots + slot;
                 if (pl.fused) {
                     ws_store4<true>(rs, prm.off_o + (pidx * D + c4 * 4) * 4u, o);
@@ -666,8 +698,9 @@ __global__ __launch_bounds__(kAttnThreads, (NQT > 1 ? 1 : 2)) void attn_kernel(c
     if (NQT == 1 && is_private && pl.n_rg_priv == 1 && pl.nsplit_pre == 0) {
         if (sh_last[0]) merge_branch<D, true, QPT, 2, true>(prm, rs, kvh, b_item, tid, 0, 1 << 30, slot, own_o, own_ml);
     } else {
-        for (int j = 0; j < nb; ++j)
-            if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
+        if (GROUPS == 1 || tid < kAttnThreads)  // the merge is written for 256 threads
+            for (int j = 0; j < nb; ++j)
+                if (sh_last[j]) merge_branch<D, true>(prm, rs, kvh, b_first + j, tid, 0, 1 << 30);  // uniform over the workgroup
     }
     __builtin_amdgcn_s_waitcnt(0);
 }
@@ -857,10 +890,11 @@ static int launch_attention(const lotts_attn_desc& d, const void* Q, const void*
     const long long items = (long long)pl.n_pre_items + pl.n_priv_items;
     if (items > 0x7fffffffLL) return LOTTS_ERR_SHAPE;
     const dim3 grid((unsigned)items), block(kAttnThreads);
-    if (d.D == 128 && pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<128, 1>), grid, block, s, prm);
-    else if (d.D == 128) LOTTS_LAUNCH((attn_kernel<128, 2>), grid, block, s, prm);
-    else if (pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<64, 1>), grid, block, s, prm);
-    else LOTTS_LAUNCH((attn_kernel<64, 2>), grid, block, s, prm);
+    const dim3 block2(2 * kAttnThreads);
+    if (d.D == 128 && pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<128, 1, 1>), grid, block, s, prm);
+    else if (d.D == 128) LOTTS_LAUNCH((attn_kernel<128, 2, 2>), grid, block2, s, prm);
+    else if (pl.nqt == 1) LOTTS_LAUNCH((attn_kernel<64, 1, 1>), grid, block, s, prm);
+    else LOTTS_LAUNCH((attn_kernel<64, 2, 2>), grid, block2, s, prm);
     if (!pl.fused) {
         const int rc = check_launch();
         if (rc != LOTTS_OK) return rc;

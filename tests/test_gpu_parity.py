@@ -47,6 +47,7 @@ SMALL_ATTN = [
     BF.with_(B=2, P=70, L=300, k=0),                                 # k = 0: decode attention
     BF.with_(B=3, Hq=16, Hkv=2, k=4, P=64, L=257),                   # G*R = 40: two row tiles
     BF.with_(B=2, Hq=40, Hkv=8, k=8, P=40, L=190),                   # G*R = 45
+    BF.with_(B=64, Hq=16, Hkv=2, k=4, P=64, L=600),                  # G*R = 40 on 128 (head, branch) pairs: eight wavefronts per item, merge in the launch
     BF.with_(B=2, Hq=32, Hkv=2, k=4, P=64, L=140),                   # G*R = 80: more than one row group
     BF.with_(B=4, Hq=8, Hkv=4, D=64, P=100, L=333, k=3),             # head_dim 64
     BF.with_(B=2, Hq=12, Hkv=2, D=64, k=6, P=31, L=95),              # head_dim 64, two row tiles
