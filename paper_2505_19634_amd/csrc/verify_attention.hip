@@ -311,7 +311,8 @@ template <int D, int NQT, int GROUPS>
 __global__ __launch_bounds__(kAttnThreads * GROUPS, (NQT > 1 ? 1 : 2)) void attn_kernel(const AttnParams prm) {
     // GROUPS = 2: eight wavefronts, two per SIMD.  The second group of four takes the second row tile; wavefront w of
     // either group streams the same key tiles, so the two share them: each loads half of a tile into a slab both
-    // read (two slabs per pair, taking turns; one workgroup barrier per tile).
+    // read (two slabs per pair, taking turns; the pair meets once per tile at a counter in LDS, the four pairs stay
+    // independent of each other).
     static_assert(GROUPS == 1 || (GROUPS == 2 && NQT == 2), "two groups split two row tiles");
     constexpr int TW = NQT / GROUPS;       // row tiles per wavefront
     constexpr int KS = D / 16;             // MFMA k-steps of the QK^T contraction
@@ -326,7 +327,7 @@ __global__ __launch_bounds__(kAttnThreads * GROUPS, (NQT > 1 ? 1 : 2)) void attn
     __shared__ __attribute__((aligned(16))) unsigned char lds[kAttnWaves * GROUPS * SLAB];
     __shared__ float sh_m[kAttnWaves * GROUPS][kRowTile];
     __shared__ float sh_l[kAttnWaves * GROUPS][kRowTile];
-    __shared__ int sh_nt[kAttnWaves * GROUPS];
+    __shared__ int sh_pair[kAttnWaves];  // GROUPS = 2: half tiles stored by the pair of wavefronts w and w + 4
 
     const int tid = threadIdx.x, wave_all = tid / kWave, lane = tid & (kWave - 1);
     const int grp = GROUPS == 1 ? 0 : wave_all / kAttnWaves;         // which row tile(s) this wavefront works on
@@ -481,33 +482,32 @@ __global__ __launch_bounds__(kAttnThreads * GROUPS, (NQT > 1 ? 1 : 2)) void attn
             for (int i = 0; i < 16; ++i) oacc[t][db][i] = 0.f;
     }
 
-    int n_loop = n_tiles;
-    if (GROUPS > 1) {  // the barrier of the tile loop needs the same trip count in every wavefront: the longest run's
-        if (lane == 0) sh_nt[wave_all] = n_tiles;
+    if (GROUPS > 1) {  // the two wavefronts of a pair count their half tiles here
+        if (tid < kAttnWaves) sh_pair[tid] = 0;
         __syncthreads();
-#pragma unroll
-        for (int w = 0; w < kAttnWaves * GROUPS; ++w) n_loop = max(n_loop, sh_nt[w]);
     }
-    for (int it = 0; it < n_loop; ++it) {
-        const bool live = GROUPS == 1 || it < n_tiles;  // uniform over the wavefront
+    for (int it = 0; it < n_tiles; ++it) {
         const bool folded = it < n_fold;
         const int kbase = folded ? run[0].lo + it * run[0].step : run[1].lo + (it - n_fold) * run[1].step;
         if (GROUPS > 1) {
             kslab = lds + ((it & 1) * kAttnWaves + wave) * SLAB;
             vslab = kslab + KSLAB;
         }
-        if (live) {
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                *reinterpret_cast<u32x4*>(kslab + ((i * GROUPS + grp) * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
-                *reinterpret_cast<u32x4*>(vslab + ((i * GROUPS + grp) * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
+        for (int i = 0; i < NLD; ++i) {
+            *reinterpret_cast<u32x4*>(kslab + ((i * GROUPS + grp) * RPI + v_row) * KSTRIDE + v_chunk * 16) = kst[i];
+            *reinterpret_cast<u32x4*>(vslab + ((i * GROUPS + grp) * RPI + v_row) * VSTRIDE + v_chunk * 16) = vst[i];
+        }
+        if (GROUPS > 1) {
+            // both halves written: the pair's counter stands at 2 * (it + 1).  Whoever gets past this has also left
+            // the tile before behind (it counted this tile only after that), so the other slab is free.
+            if (lane == 0) __hip_atomic_fetch_add(&sh_pair[wave], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            for (int spin = 0; spin < (1 << 20); ++spin) {  // the partner runs the same tiles: the wait ends; bounded all the same
+                if (__hip_atomic_load(&sh_pair[wave], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= 2 * (it + 1)) break;
+                __builtin_amdgcn_s_sleep(1);
             }
         }
-        // Both halves of the tile are in the slab; the other slab of the pair, which the next tile will overwrite, is
-        // free: whoever passes this barrier has left the tile before this one behind.
-        if (GROUPS > 1) __syncthreads();
         if (it + 1 < n_tiles) fetch(it + 1);
-        if (!live) continue;
         // K fragments (A operand of S^T = K Q^T: lane = key row ln, 8 contiguous d)
         bf16x8 kf[KS];
 #pragma unroll
