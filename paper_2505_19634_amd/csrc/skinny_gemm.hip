@@ -10,8 +10,8 @@
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
 //   skinny_gemm_wide_kernel<MT, WAVES>  more than 64 tokens, or long K runs; grid (blocks of 256 weight rows,
-//       K splits): 4 wavefronts with two row tiles each (every X fragment read from LDS feeds two MFMAs),
-//       or, for 65..224 tokens, 8 wavefronts with one row tile each (two wavefronts per SIMD).
+//       K splits): 8 wavefronts with one row tile each (two wavefronts per SIMD) up to 224 tokens; 4 wavefronts
+//       with two row tiles each (every X fragment read from LDS feeds two MFMAs) at 225..256.
 //   skinny_gemm_wide8_kernel<MT>  129..256 tokens on long K runs: the eight-wavefront shape with X brought in by
 //       global-to-LDS loads into two half-chunk stages instead of through registers.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
@@ -66,13 +66,13 @@ static inline GemmPlan plan_gemm(int M, int N, int K, long long ldx) {
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
     // The wide kernel covers 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged
-    // in LDS serves twice the rows of the narrow kernel.  It comes in two shapes.  Four wavefronts with two
-    // row tiles each (an X fragment read from LDS feeds two MFMAs): up to 64 tokens, where it wins when its
-    // workgroups still get long runs of chunks (gate+up, down) and loses on short ones (QKV, O), and at
-    // 225..256 tokens, where the accumulators leave room for one wavefront per SIMD only.  Eight wavefronts
-    // with one row tile each for 65..224 tokens: two wavefronts per SIMD hide each other's barrier and load
-    // waits, measured 4..22 % faster than the four-wavefront shape on the 32B-shaped layers.
-    pl.rt = (pl.mt >= 3 && pl.mt <= 7) ? 1 : 2;
+    // in LDS serves twice the rows of the narrow kernel.  Up to 64 tokens it wins when its workgroups still get long
+    // runs of chunks (gate+up, down) and loses on short ones (QKV, O).  It runs on eight wavefronts with one row
+    // tile each: two wavefronts per SIMD hide each other's barrier and load waits, measured 4..22 % faster on the
+    // 32B-shaped layers than four wavefronts with two row tiles each (where an X fragment read from LDS feeds two
+    // MFMAs) at every token count that fits -- 256 tokens do not (the accumulators leave room for one wavefront
+    // per SIMD only) and take the four-wavefront shape, unless the staged kernel below serves them.
+    pl.rt = pl.mt <= 7 ? 1 : 2;
     const int nb_wide = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
     const int ks_wide = plan_ksplit(nb_wide, chunks, false);
     pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
@@ -554,8 +554,8 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
         }
     } else if (pl.wide) {
         switch (pl.mt) {
-            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 4>), grid, block, s, p); break;
-            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 4>), grid, block, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 8>), grid, wide8, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 8>), grid, wide8, s, p); break;
             case 3: LOTTS_LAUNCH((skinny_gemm_wide_kernel<3, 8>), grid, wide8, s, p); break;
             case 4: LOTTS_LAUNCH((skinny_gemm_wide_kernel<4, 8>), grid, wide8, s, p); break;
             case 5: LOTTS_LAUNCH((skinny_gemm_wide_kernel<5, 8>), grid, wide8, s, p); break;
