@@ -307,6 +307,7 @@ def logit_inputs(cfg, noise_std, salt=0, bf16=False):
     (S.CONFIGS["C4"].with_(B=64), True, 1.0),                      # the branch sweep's largest point, bf16 logits
     (S.CONFIGS["C2"].with_(B=1500, V=4096, k=2), True, 1.0),       # more workgroups than the chip holds at once
     # many token decisions at a temperature other than 1
+    (S.CONFIGS["C1"].with_(B=2, V=1 << 20, k=1), True, 1.0),       # the largest vocabulary: 64 pieces per row, 512 chunks
     (S.CONFIGS["C1"].with_(B=600, V=999, k=2), False, 0.8),
     (S.CONFIGS["C1"].with_(B=300, V=4096, k=2), True, 1.3),
 ], ids=lambda x: str(x) if not hasattr(x, "B") else "B%d_k%d_V%d" % (x.B, x.k, x.V))
