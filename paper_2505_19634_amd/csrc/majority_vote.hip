@@ -64,7 +64,11 @@ __global__ __launch_bounds__(kWave) void majority_vote_wave_kernel(int B, const 
                                                                    int32_t* __restrict__ winner,
                                                                    int32_t* __restrict__ winner_count) {
     const int n = blockIdx.x, lane = threadIdx.x;
-    const int32_t ai = lane < B ? answers[(size_t)n * B + lane] : -1;
+    __builtin_assume(B >= 1);  // checked on the host; lets all arguments be fetched in one go
+    // every lane loads (lanes past B re-read the last answer): with the load under a branch on B the pointer would
+    // only be fetched after B has arrived and been compared -- one more dependent trip to the argument block
+    const int32_t av = answers[(size_t)n * B + (lane < B ? lane : B - 1)];
+    const int32_t ai = lane < B ? av : -1;
     int best = 0;
     int32_t best_a = -1;
     for (int j = 0; j < B; ++j) {  // everything in this loop is uniform over the wavefront
