@@ -581,11 +581,12 @@ __global__ __launch_bounds__(kAttnThreads * GROUPS, (NQT > 1 ? 1 : 2)) void attn
         }
     }
 
-    // ---- combine the 4 wavefronts' states (fixed order) and store the item's partial ----
-    // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier all 256
-    // threads form sum_w 2^(m_w - m) O_w and write the valid rows out, coalesced.  A thread owns QPT
-    // output quads of a row tile -- quad tid + 256 q: the same column of rows RSTEP apart -- and reads
-    // everything it needs for all of them before it uses any of it.
+    // ---- combine the 4 wavefronts' states of a row tile (fixed order) and store the item's partial ----
+    // Each wavefront parks its raw state in LDS (its slab is free now); after one barrier the 256 threads
+    // of a group of four wavefronts form sum_w 2^(m_w - m) O_w over their group and write the valid rows out,
+    // coalesced (two groups: both row tiles at the same time).  A thread owns QPT output quads of a row
+    // tile -- quad t + 256 q, t its number within the group: the same column of rows RSTEP apart -- and
+    // reads everything it needs for all of them before it uses any of it.
     constexpr int F4 = D / 4;
     constexpr int QPT = kRowTile * F4 / kAttnThreads;  // 4 (D = 128) or 2 (D = 64)
     constexpr int RSTEP = kAttnThreads / F4;
