@@ -65,6 +65,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C3", help="C2, C3, C5 or C4xB (e.g. C4x16)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-tokens", type=int, default=0,
+                    help="token count M of the weight-GEMM legs (default: the workload's B * (k + 1), at most 256)")
     ap.add_argument("--min-timed-launches", type=int, default=64,
                     help="attention launches timed in all (timed region plus a labelled leg after it)")
     args = ap.parse_args()
@@ -450,7 +452,7 @@ def main() -> int:
 
     # weight GEMMs of one 32B-shaped decoder layer for the step's M = B * (k + 1) tokens (hidden 5120,
     # 40/8 heads of 128, MLP 27648): QKV, O, gate+up, down.  Weight copies are rotated like the KV sets.
-    Mg = min(cfg.B * cfg.R, 256)
+    Mg = args.gemm_tokens if 1 <= args.gemm_tokens <= 256 else min(cfg.B * cfg.R, 256)
     gemms = {}
     for name_, (Ng, Kg) in {"qkv_proj": (7168, 5120), "o_proj": (5120, 5120), "gate_up_proj": (55296, 5120),
                             "down_proj": (5120, 27648)}.items():
