@@ -9,11 +9,9 @@
 //       slab and read back as the MFMA A operand; the X chunk (up to 256 x 128) is fetched once per
 //       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
 //       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
-//   skinny_gemm_wide_kernel<MT, WAVES>  more than 64 tokens, or long K runs; grid (blocks of 256 weight rows,
-//       K splits): 8 wavefronts with one row tile each (two wavefronts per SIMD) up to 224 tokens; 4 wavefronts
-//       with two row tiles each (every X fragment read from LDS feeds two MFMAs) at 225..256.
-//   skinny_gemm_wide8_kernel<MT>  129..256 tokens on long K runs: the eight-wavefront shape with X brought in by
-//       global-to-LDS loads into two half-chunk stages instead of through registers.
+//   skinny_gemm_stream_kernel<MT>  more than 64 tokens, or long K runs; grid (blocks of 256 weight rows, K splits):
+//       8 wavefronts with one row tile each (two wavefronts per SIMD); W and X both go from global memory straight
+//       into LDS stages of half a chunk, with no registers in between.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -43,8 +41,7 @@ struct GemmParams {
 };
 
 struct GemmPlan {
-    int mt, wide, rt, nblocks, ksplit;  // rt: row tiles per wavefront of the wide kernel (8 / wavefronts)
-    int staged;                         // X through global-to-LDS stages (skinny_gemm_wide8_kernel)
+    int mt, stream, nblocks, ksplit;  // stream: skinny_gemm_stream_kernel (256 weight rows per workgroup)
 };
 // K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
 // Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
@@ -61,31 +58,20 @@ static inline int plan_ksplit(int nblocks, int chunks, bool two_per_cu) {
     return ks < 1 ? 1 : ks;
 }
 
-static inline GemmPlan plan_gemm(int M, int N, int K, long long ldx) {
+static inline GemmPlan plan_gemm(int M, int N, int K) {
     GemmPlan pl;
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
-    // The wide kernel covers 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged
-    // in LDS serves twice the rows of the narrow kernel.  Up to 64 tokens it wins when its workgroups still get long
-    // runs of chunks (gate+up, down) and loses on short ones (QKV, O).  It runs on eight wavefronts with one row
-    // tile each: two wavefronts per SIMD hide each other's barrier and load waits, measured 4..22 % faster on the
-    // 32B-shaped layers than four wavefronts with two row tiles each (where an X fragment read from LDS feeds two
-    // MFMAs) at every token count that fits -- 256 tokens do not (the accumulators leave room for one wavefront
-    // per SIMD only) and take the four-wavefront shape, unless the staged kernel below serves them.
-    pl.rt = pl.mt <= 7 ? 1 : 2;
-    const int nb_wide = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
-    const int ks_wide = plan_ksplit(nb_wide, chunks, false);
-    pl.wide = (pl.mt > 2 || chunks / ks_wide >= 16) ? 1 : 0;
-    pl.staged = 0;
-    if (pl.wide) {
-        pl.nblocks = nb_wide;
-        pl.ksplit = ks_wide;
-        // The staged kernel, where it measured faster on the 32B-shaped layers (gate+up: 40 chunks per workgroup,
-        // from 129 tokens; down: 18, from 161; QKV and O: 5..10, at 225..256 only), and where a lane's byte offset
-        // into X fits the 32 bits its loads take.
-        const int run = chunks / pl.ksplit;
-        const bool pays = pl.mt == 8 || (pl.mt >= 5 && run >= 32) || (pl.mt >= 6 && run >= 16);
-        pl.staged = (pays && (long long)(M - 1) * ldx * 2 + 256 < (1LL << 32)) ? 1 : 0;
+    // The streaming kernel covers 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged in LDS
+    // serves twice the rows of the narrow kernel.  Up to 64 tokens it wins when its workgroups still get long runs
+    // of chunks (gate+up, down on the 32B-shaped layers) and loses on short ones (QKV, O); above 64 tokens the
+    // narrow kernel's registers do not hold the accumulators of two workgroups per unit, and it always runs.
+    const int nb_stream = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
+    const int ks_stream = plan_ksplit(nb_stream, chunks, false);
+    pl.stream = (pl.mt > 2 || chunks / ks_stream >= 16) ? 1 : 0;
+    if (pl.stream) {
+        pl.nblocks = nb_stream;
+        pl.ksplit = ks_stream;
     } else {
         pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
         pl.ksplit = plan_ksplit(pl.nblocks, chunks, true);
@@ -156,7 +142,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
             fetch_w(c + 2, w);
         }
         // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k); the fragments of
-        // step s + 1 are requested before the MFMAs of step s (see the wide kernel)
+        // step s + 1 are requested before the MFMAs of step s, so that LDS reads and matrix work overlap
         auto frags = [&](int s, g_bf16x8& a, g_bf16x8 (&b)[MT]) {
             a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
 #pragma unroll
@@ -209,266 +195,133 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
     }
 }
 
-// More than 64 tokens, and long K runs at any M.  A workgroup of WAVES wavefronts covers 256 weight rows:
-// each wavefront owns RT = 8 / WAVES MFMA row tiles (32 * RT rows) and all M tokens; with RT = 2 an X
-// fragment read from LDS feeds two MFMAs.  One W chunk (8 KB * RT per wavefront) is in flight while the
-// previous one is multiplied, as in the attention kernel; one X tile in LDS, rewritten behind a barrier
-// once every wavefront has finished with it.
-template <int MT, int WAVES>
-__global__ __launch_bounds__(WAVES * kWave, 1) void skinny_gemm_wide_kernel(const GemmParams p) {
-    constexpr int RT = 8 / WAVES;
-    constexpr int kThreads = WAVES * kWave;
-    constexpr int WROWS = 32 * RT;
-    constexpr int XROWS = 32 * MT;
-    constexpr int XPT = (XROWS * 16 + kThreads - 1) / kThreads;  // 16-byte pieces of an X chunk per thread
-    __shared__ __attribute__((aligned(16))) unsigned char xbuf[XROWS * kGemmRowBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[WAVES][WROWS * kGemmRowBytes];
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
-    const int ln = lane & 31, hh = lane >> 5;
-    const int n0 = blockIdx.x * (WAVES * WROWS) + wave * WROWS;
-    const int chunks = p.K / kGemmChunk;
-    const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
-    const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
-    unsigned char* wslab = wslab_all[wave];
-
-    const int w_row = lane >> 4, w_ch = lane & 15;  // a load instruction covers 4 whole 256-byte row pieces
-    g_u32x4 wst[8 * RT], xst[XPT];
-    auto fetch_w = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < 8 * RT; ++i) {
-            int n = n0 + i * 4 + w_row;
-            n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
-            wst[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
-        }
-    };
-    auto fetch_x = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            const int idx = tid + i * kThreads;
-            int m = idx >> 4;
-            m = m < p.M ? m : p.M - 1;
-            xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
-        }
-    };
-    g_f32x16 acc[RT][MT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[r][t][i] = 0.f;
-
-    if (c_lo < c_hi) {
-        fetch_x(c_lo);  // X before W: loads complete in issue order and X is wanted first
-        fetch_w(c_lo);
-    }
-    for (int c = c_lo; c < c_hi; ++c) {
-        __syncthreads();  // every wavefront has multiplied the previous chunk out of the X tile
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            const int idx = tid + i * kThreads;
-            if (idx < XROWS * 16)  // the last piece of a thread may lie past the tile when 512 threads share it
-                *reinterpret_cast<g_u32x4*>(xbuf + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
-        }
-        __syncthreads();  // the X chunk is complete
-#pragma unroll
-        for (int i = 0; i < 8 * RT; ++i)
-            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
-        if (c + 1 < c_hi) {
-            fetch_x(c + 1);
-            fetch_w(c + 1);
-        }
-        // Y^T[n][m] += sum_k W[n][k] X[m][k]: RT W fragments per k step, every X fragment feeds RT MFMAs.
-        // The fragments of step s + 1 are requested before the MFMAs of step s are issued (the scheduling
-        // barriers keep the compiler from sinking each read down to its use, where it would be waited for
-        // with nothing else in flight: at most two wavefronts per SIMD are too few to hide an LDS latency).
-        auto frags = [&](int s, g_bf16x8 (&a)[RT], g_bf16x8 (&b)[MT]) {
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                a[r] = *reinterpret_cast<const g_bf16x8*>(wslab + (r * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-                b[t] = *reinterpret_cast<const g_bf16x8*>(xbuf + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
-        };
-        // Two fragment sets, or one where registers run out: at 256 tokens, and at 224 with two wavefronts
-        // per SIMD (256 registers each).
-        constexpr int NF = (MT <= 7 && !(WAVES == 8 && MT >= 7)) ? 2 : 1;
-        g_bf16x8 fa[NF][RT], fb[NF][MT];
-        if (NF == 2) frags(0, fa[0], fb[0]);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            if (NF == 2) {
-                if (s + 1 < 8) frags(s + 1, fa[(s + 1) & (NF - 1)], fb[(s + 1) & (NF - 1)]);
-            } else {
-                frags(s, fa[0], fb[0]);  // all reads of the step first, then the MFMAs as their operands arrive
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-#pragma unroll
-                for (int r = 0; r < RT; ++r)
-                    acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)][r], fb[s & (NF - 1)][t], acc[r][t], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    // register i of this lane: output row m = t * 32 + ln, column n = n0 + r * 32 + (i / 4) * 8 + hh * 4 + i % 4
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            const int m = t * 32 + ln;
-            if (m >= p.M) continue;
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int n = n0 + r * 32 + q4 * 8 + hh * 4;
-                if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
-                if (p.ksplit == 1) {
-                    g_bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[r][t][q4 * 4 + e];
-                    *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
-                } else {
-                    *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) =
-                        make_float4(acc[r][t][q4 * 4 + 0], acc[r][t][q4 * 4 + 1], acc[r][t][q4 * 4 + 2],
-                                    acc[r][t][q4 * 4 + 3]);
-                }
-            }
-        }
-}
-
-// Many tokens on long K runs (see plan_gemm): eight wavefronts (two per SIMD), each with one MFMA row tile of 32
-// weight rows and all M tokens, as the eight-wavefront shape of the kernel above.  W as there: one chunk (8 KB per
-// wavefront) in flight in registers while the previous one is multiplied out of the wavefront's LDS slab.  X does
-// not pass through registers: global-to-LDS loads (16 bytes per lane, written at a wavefront-uniform LDS base +
-// 16 * lane) fill one of two half-chunk stages (64 k each) while the other is multiplied, one barrier per stage.
-// That frees the 32 registers (256 tokens then fit two wavefronts per SIMD) and the LDS store instructions the X
-// staging takes, and halves the lead of the X prefetch (half a chunk instead of one): a gain where a chunk takes
-// long (many tokens, long runs), a loss where it is short.  A stage keeps rows of 128 bytes back to back (a load instruction
-// fills 8 whole rows), so the 16-byte pieces of a row are stored permuted -- piece p of row r at slot
-// p ^ ((r >> 1) & 7) -- which spreads the 16 lanes of a fragment read over all 64 banks.
+// Long K runs at any token count, and every launch with more than 64 tokens.  Eight wavefronts (two per SIMD),
+// 256 weight rows per workgroup, one workgroup per unit: each wavefront owns one MFMA row tile of 32 weight rows and
+// all M tokens.  Neither operand passes through registers: global-to-LDS loads (16 bytes per lane, landing at a
+// wavefront-uniform LDS base + 16 * lane) fill stages of half a chunk (64 k) --
+//   X: two stages per workgroup, one multiplied while the other is filled, one barrier per stage;
+//   W: three stages per wavefront (32 rows x 64 k, 4 KB): one multiplied, two on their way, so that a W transfer has
+//      a whole chunk of time to arrive from HBM; wavefront-private, non-temporal.
+// A stage keeps rows of 128 bytes back to back (a load instruction fills 8 whole rows), so the 16-byte pieces of a
+// row are stored permuted -- piece p of row r at slot p ^ ((r >> 1) & 7) -- which spreads the 16 lanes of a
+// fragment read over all 64 banks without padding.  With no staging registers there is room for two fragment sets
+// beside the accumulators of 256 tokens: the LDS reads of k step s + 1 run under the MFMAs of step s.
+//
+// The loads are written out as instructions.  Through the compiler's builtin every later LDS access of the kernel
+// would wait for ALL loads in flight (the compiler cannot tell which LDS bytes a transfer writes), which stalls the
+// transfers that are meant to stay in flight; and without a "memory" clobber, with which the same wait comes
+// back: the barrier statements of the step loop, which have it, fence every read of a stage against the transfer
+// that refills it, and volatile statements keep their order among themselves.  M0 carries the LDS base.  Since the
+// compiler does not know of the loads, the waits are written out too: before the barrier of a step, vmcnt(4) -- the
+// step's X transfers have landed, and with them the older W stage; only the 4 W transfers issued after them (the
+// next step's stage) may still be in flight -- or vmcnt(0) in the last step, after which nothing was issued.
 template <int MT>
-__global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_wide8_kernel(const GemmParams p) {
+__global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const GemmParams p) {
     constexpr int XROWS = 32 * MT;
-    constexpr int XINSTR = XROWS / 8;            // load instructions per stage, dealt to the 8 wavefronts
-    constexpr int XI = (XINSTR + 7) / 8;         // at most this many per wavefront
-    constexpr int kStageRow = 128;               // bytes per row of a stage
-    __shared__ __attribute__((aligned(1024))) unsigned char xs0[XROWS * kStageRow];
-    __shared__ __attribute__((aligned(1024))) unsigned char xs1[XROWS * kStageRow];
-    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[8][32 * kGemmRowBytes];
+    constexpr int XINSTR = XROWS / 8;
+    constexpr int XI = (XINSTR + 7) / 8;
+    constexpr int kStageRow = 128;
+    constexpr int XSTAGE = XROWS * kStageRow, WSTAGE = 32 * kStageRow;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * XSTAGE + 8 * 3 * WSTAGE];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31, hh = lane >> 5;
     const int n0 = blockIdx.x * 256 + wave * 32;
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
-    unsigned char* wslab = wslab_all[wave];
+    const int G = 2 * (c_hi - c_lo);  // half-chunk steps
+    unsigned char* xs = lds;
+    unsigned char* wsl = lds + 2 * XSTAGE + wave * 3 * WSTAGE;
 
-    const int w_row = lane >> 4, w_ch = lane & 15;  // a W load instruction covers 4 whole 256-byte row pieces
-    g_u32x4 wst[8];
-    auto fetch_w = [&](int c) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int n = n0 + i * 4 + w_row;
-            n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
-            wst[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
-        }
-    };
-    // lane -> (row of the instruction's 8, slot); the piece fetched for a slot is slot ^ swizzle(row).  The byte
-    // offset of the lane's piece inside a half chunk of X is the same for every chunk: a 32-bit register per
-    // instruction (the host checks that it fits), on top of a scalar base that moves along K.
-    const int x_row = lane >> 3, x_slot = lane & 7;
-    unsigned x_off[XI];
+    // Per-lane source addresses of the transfers, for K offset 0 of the workgroup's range: 64-bit, so that neither
+    // operand is limited to 4 GB.  lane -> (row of the instruction's 8, slot); the piece fetched for a slot is
+    // slot ^ swizzle(row).
+    const int l_row = lane >> 3, l_slot = lane & 7;
+    const __bf16* x_src[XI];
+    const __bf16* w_src[4];
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
-        const int r = (wave + i * 8) * 8 + x_row;
+        const int r = (wave + i * 8) * 8 + l_row;
         const int m = r < p.M ? r : p.M - 1;
-        x_off[i] = (unsigned)((long long)m * p.ldx * 2) + (unsigned)((x_slot ^ ((r >> 1) & 7)) * 16);
+        x_src[i] = p.X + (long long)m * p.ldx + (long long)c_lo * kGemmChunk + (l_slot ^ ((r >> 1) & 7)) * 8;
     }
-    auto fetch_x = [&](int c, int half, unsigned char* stage) {
-        const __bf16* base = p.X + (long long)c * kGemmChunk + half * 64;  // uniform
 #pragma unroll
-        for (int i = 0; i < XI; ++i) {
-            const int j = wave + i * 8;  // uniform over the wavefront
-            if (j < XINSTR) {
-                // Written as an instruction: through the builtin the compiler makes every later LDS access of the
-                // kernel wait for ALL loads in flight (it cannot tell which LDS bytes the transfer writes), which
-                // would stall the W chunk that is meant to stay in flight.  M0 carries the LDS base.  No "memory"
-                // clobber (with one the compiler again waits for everything before the next LDS read): the
-                // barrier statements of the chunk loop, which have it, fence every read of a stage against the
-                // transfer that refills it, and volatile statements keep their order among themselves.
-                const unsigned lds_base = __builtin_amdgcn_readfirstlane(
-                    (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)(stage + j * 8 * kStageRow));
+    for (int i = 0; i < 4; ++i) {
+        const int r = i * 8 + l_row;
+        int n = n0 + r;
+        n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
+        w_src[i] = p.W + (long long)n * p.ldw + (long long)c_lo * kGemmChunk + (l_slot ^ ((r >> 1) & 7)) * 8;
+    }
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // M0 is on the clobber list on purpose
-                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+    auto fetch_x = [&](int g) {
+        unsigned char* stage = xs + (g & 1) * XSTAGE;
+#pragma unroll
+        for (int i = 0; i < XI; ++i) {
+            const int j = wave + i * 8;
+            if (j < XINSTR) {
+                const unsigned lds_base = __builtin_amdgcn_readfirstlane(
+                    (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)(stage + j * 8 * kStageRow));
+                asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                              :
-                             : "v"(x_off[i]), "s"(base), "s"(lds_base)
+                             : "v"(x_src[i] + (long long)g * 64), "s"(lds_base)
                              : "m0");
-#pragma clang diagnostic pop
             }
         }
     };
+    auto fetch_w = [&](int g) {
+        unsigned char* stage = wsl + (g % 3) * WSTAGE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned lds_base = __builtin_amdgcn_readfirstlane(
+                (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)(stage + i * 8 * kStageRow));
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+                         :
+                         : "v"(w_src[i] + (long long)g * 64), "s"(lds_base)
+                         : "m0");
+        }
+    };
+#pragma clang diagnostic pop
     g_f32x16 acc[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    const int swz = (ln >> 1) & 7;  // (row >> 1) & 7 of this lane's rows t * 32 + ln
-    // four k steps of one stage: the W fragment comes from k steps 4 * half .. of the slab, the X fragments from the stage
-    auto multiply = [&](int half, const unsigned char* stage) {
-        constexpr int NF = MT <= 6 ? 2 : 1;  // two fragment sets while 256 registers hold them
-        g_bf16x8 fa[NF], fb[NF][MT];
+    const int swz = (ln >> 1) & 7;
+    auto multiply = [&](const unsigned char* xst, const unsigned char* wst) {
+        g_bf16x8 fa[2], fb[2][MT];
         auto frags = [&](int s, g_bf16x8& a, g_bf16x8 (&b)[MT]) {
-            a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * (4 * half + s) + hh) * 16);
+            a = *reinterpret_cast<const g_bf16x8*>(wst + ln * kStageRow + (((2 * s + hh) ^ swz) * 16));
 #pragma unroll
             for (int t = 0; t < MT; ++t)
-                b[t] = *reinterpret_cast<const g_bf16x8*>(stage + (t * 32 + ln) * kStageRow + (((2 * s + hh) ^ swz) * 16));
+                b[t] = *reinterpret_cast<const g_bf16x8*>(xst + (t * 32 + ln) * kStageRow + (((2 * s + hh) ^ swz) * 16));
         };
-        if (NF == 2) frags(0, fa[0], fb[0]);
+        frags(0, fa[0], fb[0]);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            if (NF == 2) {
-                if (s + 1 < 4) frags(s + 1, fa[(s + 1) & (NF - 1)], fb[(s + 1) & (NF - 1)]);
-            } else {
-                frags(s, fa[0], fb[0]);
-            }
+            if (s + 1 < 4) frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < MT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & (NF - 1)], fb[s & (NF - 1)][t], acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1], fb[s & 1][t], acc[t], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-
-    if (c_lo < c_hi) {
-        fetch_x(c_lo, 0, xs0);
-        fetch_w(c_lo);
+    if (G > 0) {
+        fetch_x(0);
+        fetch_w(0);
+        fetch_w(1);  // G is even: step 1 exists
     }
-    // The waits before the barriers are written out: a wavefront's global-to-LDS loads count in vmcnt like its
-    // other loads, in issue order, and a stage must have landed before the barrier that publishes it.
-    for (int c = c_lo; c < c_hi; ++c) {
-        const bool more = c + 1 < c_hi;  // uniform
-        // first half of chunk c: its X stage and W chunk c have been requested and nothing else is in flight
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // everybody's part of xs0 has landed; xs1 is free
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = wst[i];
-        fetch_x(c, 1, xs1);
-        __builtin_amdgcn_sched_barrier(0);  // the wait below counts on this order: the stage's loads, then the 8 of W
-        if (more) fetch_w(c + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(0, xs0);
-        // second half: the stage requested above has landed; the 8 W loads issued after it, if any, stay in flight
-        if (more)
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // xs1 has landed; xs0 is free
+    for (int g = 0; g < G; ++g) {
+        // issued after step g's X: the 4 W transfers of step g + 1, unless there is none
+        if (g + 1 < G)
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         else
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (more) fetch_x(c + 1, 0, xs0);
-        multiply(1, xs1);
+        if (g + 1 < G) fetch_x(g + 1);
+        if (g + 2 < G) fetch_w(g + 2);
+        multiply(xs + (g & 1) * XSTAGE, wsl + (g % 3) * WSTAGE);
     }
     // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
 #pragma unroll
@@ -521,7 +374,7 @@ static inline bool gemm_sizes_ok(int M, int N, int K) {
 
 extern "C" size_t skinny_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) {
     if (!lotts::gemm_sizes_ok(M, N, K)) return 0;
-    const lotts::GemmPlan pl = lotts::plan_gemm(M, N, K, K);  // the K split does not depend on the row pitch of X
+    const lotts::GemmPlan pl = lotts::plan_gemm(M, N, K);
     const size_t bytes = pl.ksplit > 1 ? (size_t)pl.ksplit * M * N * sizeof(float) : 0;
     return bytes < 256 ? 256 : bytes;
 }
@@ -534,7 +387,7 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     if (ldx < K || ldw < K || ldy < N || (ldx % 8) || (ldw % 8) || (ldy % 4)) return LOTTS_ERR_SHAPE;
     if ((((uintptr_t)X | (uintptr_t)W | (uintptr_t)workspace) & 15) || ((uintptr_t)Y & 7)) return LOTTS_ERR_SHAPE;
     if (workspace_bytes < skinny_gemm_workspace_bytes(M, N, K)) return LOTTS_ERR_WORKSPACE;
-    GemmPlan pl = plan_gemm(M, N, K, ldx);
+    const GemmPlan pl = plan_gemm(M, N, K);
     GemmParams p;
 
     p.X = static_cast<const __bf16*>(X);
@@ -544,24 +397,17 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit;
     p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads), wide8(8 * kWave);
-    if (pl.staged) {
+    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads), block8(8 * kWave);
+    if (pl.stream) {
         switch (pl.mt) {
-            case 5: LOTTS_LAUNCH((skinny_gemm_wide8_kernel<5>), grid, wide8, s, p); break;
-            case 6: LOTTS_LAUNCH((skinny_gemm_wide8_kernel<6>), grid, wide8, s, p); break;
-            case 7: LOTTS_LAUNCH((skinny_gemm_wide8_kernel<7>), grid, wide8, s, p); break;
-            default: LOTTS_LAUNCH((skinny_gemm_wide8_kernel<8>), grid, wide8, s, p); break;
-        }
-    } else if (pl.wide) {
-        switch (pl.mt) {
-            case 1: LOTTS_LAUNCH((skinny_gemm_wide_kernel<1, 8>), grid, wide8, s, p); break;
-            case 2: LOTTS_LAUNCH((skinny_gemm_wide_kernel<2, 8>), grid, wide8, s, p); break;
-            case 3: LOTTS_LAUNCH((skinny_gemm_wide_kernel<3, 8>), grid, wide8, s, p); break;
-            case 4: LOTTS_LAUNCH((skinny_gemm_wide_kernel<4, 8>), grid, wide8, s, p); break;
-            case 5: LOTTS_LAUNCH((skinny_gemm_wide_kernel<5, 8>), grid, wide8, s, p); break;
-            case 6: LOTTS_LAUNCH((skinny_gemm_wide_kernel<6, 8>), grid, wide8, s, p); break;
-            case 7: LOTTS_LAUNCH((skinny_gemm_wide_kernel<7, 8>), grid, wide8, s, p); break;
-            default: LOTTS_LAUNCH((skinny_gemm_wide_kernel<8, 4>), grid, block, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_stream_kernel<1>), grid, block8, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_stream_kernel<2>), grid, block8, s, p); break;
+            case 3: LOTTS_LAUNCH((skinny_gemm_stream_kernel<3>), grid, block8, s, p); break;
+            case 4: LOTTS_LAUNCH((skinny_gemm_stream_kernel<4>), grid, block8, s, p); break;
+            case 5: LOTTS_LAUNCH((skinny_gemm_stream_kernel<5>), grid, block8, s, p); break;
+            case 6: LOTTS_LAUNCH((skinny_gemm_stream_kernel<6>), grid, block8, s, p); break;
+            case 7: LOTTS_LAUNCH((skinny_gemm_stream_kernel<7>), grid, block8, s, p); break;
+            default: LOTTS_LAUNCH((skinny_gemm_stream_kernel<8>), grid, block8, s, p); break;
         }
     } else if (pl.mt == 1) {
         LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);
