@@ -197,11 +197,15 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
 
 // Long K runs at any token count, and every launch with more than 64 tokens.  Eight wavefronts (two per SIMD),
 // 256 weight rows per workgroup, one workgroup per unit: each wavefront owns one MFMA row tile of 32 weight rows and
-// all M tokens.  Neither operand passes through registers: global-to-LDS loads (16 bytes per lane, landing at a
+// all M tokens -- or, for an even number of token tiles from 4 on (97..128, 161..192, 225..256 tokens), two
+// neighbouring wavefronts own two row tiles together and half of the token tiles each: a k step then reads
+// 2 + MT / 2 fragments for MT MFMAs instead of 1 + MT, and LDS reads are what bounds the loop at these token counts
+// (measured 1..11 % faster on the 32B-shaped layers).  Neither operand passes through registers: global-to-LDS loads (16 bytes per lane, landing at a
 // wavefront-uniform LDS base + 16 * lane) fill stages of half a chunk (64 k) --
 //   X: two stages per workgroup, one multiplied while the other is filled, one barrier per stage;
 //   W: three stages per wavefront (32 rows x 64 k, 4 KB): one multiplied, two on their way, so that a W transfer has
-//      a whole chunk of time to arrive from HBM; wavefront-private, non-temporal.
+//      a whole chunk of time to arrive from HBM; non-temporal; private to the wavefront, or to the pair (each
+//      fills its half of the pair's stage; the step barrier that publishes X publishes these too).
 // A stage keeps rows of 128 bytes back to back (a load instruction fills 8 whole rows), so the 16-byte pieces of a
 // row are stored permuted -- piece p of row r at slot p ^ ((r >> 1) & 7) -- which spreads the 16 lanes of a
 // fragment read over all 64 banks without padding.  With no staging registers there is room for two fragment sets
@@ -215,8 +219,10 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
 // compiler does not know of the loads, the waits are written out too: before the barrier of a step, vmcnt(4) -- the
 // step's X transfers have landed, and with them the older W stage; only the 4 W transfers issued after them (the
 // next step's stage) may still be in flight -- or vmcnt(0) in the last step, after which nothing was issued.
-template <int MT>
+template <int MT, int RT>
 __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const GemmParams p) {
+    static_assert(RT == 1 || (RT == 2 && MT % 2 == 0), "a pair of wavefronts splits the token tiles evenly");
+    constexpr int TT = MT / RT;  // token tiles per wavefront
     constexpr int XROWS = 32 * MT;
     constexpr int XINSTR = XROWS / 8;
     constexpr int XI = (XINSTR + 7) / 8;
@@ -225,13 +231,16 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * XSTAGE + 8 * 3 * WSTAGE];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31, hh = lane >> 5;
-    const int n0 = blockIdx.x * 256 + wave * 32;
+    // RT = 1: wavefront w owns row tile w and all tokens.  RT = 2: wavefronts 2j and 2j + 1 own row tiles 2j and
+    // 2j + 1 together, each half of the token tiles, and share the W stages of their 64 rows.
+    const int grp = RT == 1 ? wave : wave >> 1, th = RT == 1 ? 0 : wave & 1;
+    const int n0 = blockIdx.x * 256 + grp * (32 * RT);
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
     const int G = 2 * (c_hi - c_lo);  // half-chunk steps
     unsigned char* xs = lds;
-    unsigned char* wsl = lds + 2 * XSTAGE + wave * 3 * WSTAGE;
+    unsigned char* wsl = lds + 2 * XSTAGE + grp * (3 * RT * WSTAGE);
 
     // Per-lane source addresses of the transfers, for K offset 0 of the workgroup's range: 64-bit, so that neither
     // operand is limited to 4 GB.  lane -> (row of the instruction's 8, slot); the piece fetched for a slot is
@@ -247,7 +256,7 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int r = i * 8 + l_row;
+        const int r = th * 32 + i * 8 + l_row;  // of a pair, each wavefront brings in 32 of the 64 rows
         int n = n0 + r;
         n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
         w_src[i] = p.W + (long long)n * p.ldw + (long long)c_lo * kGemmChunk + (l_slot ^ ((r >> 1) & 7)) * 8;
@@ -270,7 +279,7 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
         }
     };
     auto fetch_w = [&](int g) {
-        unsigned char* stage = wsl + (g % 3) * WSTAGE;
+        unsigned char* stage = wsl + (g % 3) * (RT * WSTAGE) + th * WSTAGE;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const unsigned lds_base = __builtin_amdgcn_readfirstlane(
@@ -282,20 +291,25 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
         }
     };
 #pragma clang diagnostic pop
-    g_f32x16 acc[MT];
+    g_f32x16 acc[RT][TT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int r = 0; r < RT; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+        for (int t = 0; t < TT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][t][i] = 0.f;
 
     const int swz = (ln >> 1) & 7;
     auto multiply = [&](const unsigned char* xst, const unsigned char* wst) {
-        g_bf16x8 fa[2], fb[2][MT];
-        auto frags = [&](int s, g_bf16x8& a, g_bf16x8 (&b)[MT]) {
-            a = *reinterpret_cast<const g_bf16x8*>(wst + ln * kStageRow + (((2 * s + hh) ^ swz) * 16));
+        g_bf16x8 fa[2][RT], fb[2][TT];
+        auto frags = [&](int s, g_bf16x8 (&a)[RT], g_bf16x8 (&b)[TT]) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-                b[t] = *reinterpret_cast<const g_bf16x8*>(xst + (t * 32 + ln) * kStageRow + (((2 * s + hh) ^ swz) * 16));
+            for (int r = 0; r < RT; ++r)
+                a[r] = *reinterpret_cast<const g_bf16x8*>(wst + (r * 32 + ln) * kStageRow + (((2 * s + hh) ^ swz) * 16));
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+                b[t] = *reinterpret_cast<const g_bf16x8*>(xst + ((th * TT + t) * 32 + ln) * kStageRow +
+                                                          (((2 * s + hh) ^ swz) * 16));
         };
         frags(0, fa[0], fb[0]);
 #pragma unroll
@@ -303,8 +317,11 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
             if (s + 1 < 4) frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1], fb[s & 1][t], acc[t], 0, 0, 0);
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < TT; ++t)
+                    acc[r][t] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][r], fb[s & 1][t], acc[r][t], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -321,27 +338,30 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         if (g + 1 < G) fetch_x(g + 1);
         if (g + 2 < G) fetch_w(g + 2);
-        multiply(xs + (g & 1) * XSTAGE, wsl + (g % 3) * WSTAGE);
+        multiply(xs + (g & 1) * XSTAGE, wsl + (g % 3) * (RT * WSTAGE));
     }
-    // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
+    // register i of accumulator (r, t) of this lane: output row m = (th * TT + t) * 32 + ln,
+    // column n = n0 + r * 32 + (i / 4) * 8 + hh * 4 + i % 4
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const int m = t * 32 + ln;
+    for (int t = 0; t < TT; ++t) {
+        const int m = (th * TT + t) * 32 + ln;
         if (m >= p.M) continue;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int n = n0 + q4 * 8 + hh * 4;
-            if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
-            if (p.ksplit == 1) {
-                g_bf16x4 o;
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[t][q4 * 4 + e];
-                *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
-            } else {
-                *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) =
-                    make_float4(acc[t][q4 * 4 + 0], acc[t][q4 * 4 + 1], acc[t][q4 * 4 + 2], acc[t][q4 * 4 + 3]);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int n = n0 + r * 32 + q4 * 8 + hh * 4;
+                if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
+                if (p.ksplit == 1) {
+                    g_bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[r][t][q4 * 4 + e];
+                    *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
+                } else {
+                    *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) = make_float4(
+                        acc[r][t][q4 * 4 + 0], acc[r][t][q4 * 4 + 1], acc[r][t][q4 * 4 + 2], acc[r][t][q4 * 4 + 3]);
+                }
             }
-        }
     }
 }
 
@@ -400,14 +420,14 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads), block8(8 * kWave);
     if (pl.stream) {
         switch (pl.mt) {
-            case 1: LOTTS_LAUNCH((skinny_gemm_stream_kernel<1>), grid, block8, s, p); break;
-            case 2: LOTTS_LAUNCH((skinny_gemm_stream_kernel<2>), grid, block8, s, p); break;
-            case 3: LOTTS_LAUNCH((skinny_gemm_stream_kernel<3>), grid, block8, s, p); break;
-            case 4: LOTTS_LAUNCH((skinny_gemm_stream_kernel<4>), grid, block8, s, p); break;
-            case 5: LOTTS_LAUNCH((skinny_gemm_stream_kernel<5>), grid, block8, s, p); break;
-            case 6: LOTTS_LAUNCH((skinny_gemm_stream_kernel<6>), grid, block8, s, p); break;
-            case 7: LOTTS_LAUNCH((skinny_gemm_stream_kernel<7>), grid, block8, s, p); break;
-            default: LOTTS_LAUNCH((skinny_gemm_stream_kernel<8>), grid, block8, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_stream_kernel<1, 1>), grid, block8, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_stream_kernel<2, 1>), grid, block8, s, p); break;
+            case 3: LOTTS_LAUNCH((skinny_gemm_stream_kernel<3, 1>), grid, block8, s, p); break;
+            case 4: LOTTS_LAUNCH((skinny_gemm_stream_kernel<4, 2>), grid, block8, s, p); break;
+            case 5: LOTTS_LAUNCH((skinny_gemm_stream_kernel<5, 1>), grid, block8, s, p); break;
+            case 6: LOTTS_LAUNCH((skinny_gemm_stream_kernel<6, 2>), grid, block8, s, p); break;
+            case 7: LOTTS_LAUNCH((skinny_gemm_stream_kernel<7, 1>), grid, block8, s, p); break;
+            default: LOTTS_LAUNCH((skinny_gemm_stream_kernel<8, 2>), grid, block8, s, p); break;
         }
     } else if (pl.mt == 1) {
         LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);
