@@ -515,7 +515,8 @@ def test_confidence_vote(lotts, oracle, N, B, T):
 # ---------------------------------------------------------------------------- weight GEMM of the verify forward
 @pytest.mark.parametrize("M,N,K", [
     (64, 512, 1024), (40, 136, 256), (5, 8, 128), (1, 1000, 384), (128, 256, 512), (97, 264, 640),
-    (129, 520, 384), (192, 2048, 2048), (256, 640, 1280), (231, 136, 128),   # more than 128 tokens: one X tile, two barriers
+    (129, 520, 384), (192, 2048, 2048), (256, 640, 1280), (231, 136, 128),   # 5, 6 and 8 token tiles
+    (170, 1032, 768),       # pairs of wavefronts with three token tiles each, the last one ragged; 8 weight rows in the last block
     (192, 11008, 2048),     # 3B-shaped MLP up projection for B = 64 branches, k = 2
     (64, 7168, 5120),       # 32B-shaped QKV projection for B * (k + 1) = 64 tokens (K split over workgroups)
     (64, 5120, 27648),      # 32B-shaped MLP down projection
@@ -527,9 +528,9 @@ def test_confidence_vote(lotts, oracle, N, B, T):
     (256, 5120, 27648),     # 32B-shaped down projection at the largest token count
     (224, 296, 896),        # seven token tiles on eight wavefronts, weight rows past the end, 7 chunks
     (199, 1288, 1152),      # a ragged seventh token tile: X pieces past the tile are fetched and not staged
-    (160, 55296, 5120),     # 32B-shaped gate+up projection on the eight-wavefront form
-    (199, 27656, 5120),     # X through global-to-LDS stages: a ragged seventh token tile, 8 weight rows in the last block, K split in two
-    (130, 55432, 4224),     # the same kernel with five token tiles, 33 chunks per workgroup, no K split
+    (160, 55296, 5120),     # 32B-shaped gate+up projection with five token tiles (no pairs)
+    (199, 27656, 5120),     # a ragged seventh token tile, 8 weight rows in the last block, K split in two
+    (130, 55432, 4224),     # five token tiles, 33 chunks per workgroup, no K split
 ])
 def test_skinny_gemm(lotts, oracle, M, N, K):
     print("gemm case", M, N, K, flush=True)
