@@ -200,8 +200,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
 // all M tokens -- or, for an even number of token tiles from 4 on (97..128, 161..192, 225..256 tokens), two
 // neighbouring wavefronts own two row tiles together and half of the token tiles each: a k step then reads
 // 2 + MT / 2 fragments for MT MFMAs instead of 1 + MT, and LDS reads are what bounds the loop at these token counts
-// (measured 1..11 % faster on the 32B-shaped layers).  Neither operand passes through registers: global-to-LDS loads (16 bytes per lane, landing at a
-// wavefront-uniform LDS base + 16 * lane) fill stages of half a chunk (64 k) --
+// (measured 1..11 % faster on the 32B-shaped layers).
+// Neither operand passes through registers: global-to-LDS loads (16 bytes per lane, landing at a wavefront-uniform
+// LDS base + 16 * lane) fill stages of half a chunk (64 k) --
 //   X: two stages per workgroup, one multiplied while the other is filled, one barrier per stage;
 //   W: three stages per wavefront (32 rows x 64 k, 4 KB): one multiplied, two on their way, so that a W transfer has
 //      a whole chunk of time to arrive from HBM; non-temporal; private to the wavefront, or to the pair (each
