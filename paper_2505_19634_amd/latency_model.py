@@ -16,10 +16,12 @@ are outside this library); the draft model's gamma sequential steps cost `draft_
 one-token step of the target each (an assumption: a draft model a tenth of the target's size).
 
     python -m paper_2505_19634_amd.latency_model --shape 3B --budget-s 4
+    python -m paper_2505_19634_amd.latency_model --shape 32B --budget-s 20 --full-model 16,3
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 from dataclasses import dataclass
@@ -110,6 +112,89 @@ class StepTimer:
         return out
 
 
+class FullModel:
+    """Every layer of a decoder shape resident on one GPU -- its bf16 weights (62 GB for the 32B shape) and the KV
+    caches of B branches, each layer its own memory -- and one verify step of the whole stack as one captured graph:
+    per layer the QKV projection, verify_attention on the Q columns of its output, the O projection, gate+up, and
+    down on the first half of gate+up's output (norms, rotary embedding, activation and KV append are outside this
+    library, so the values that flow are not a language model's; the shapes, the memory traffic and the launch
+    sequence are), then the LM head and the acceptance from logits.  Replaying the graph gives the step's device
+    time with the gaps between launches and with nothing left in a cache by an earlier use of the same weights:
+    the check on StepTimer's sum of isolated kernel times."""
+
+    def __init__(self, shape: ModelShape, prefix: int, private: int, B: int, gamma: int, device="cuda:0"):
+        s, R = shape, gamma + 1
+        M = B * R
+        if M > 256:
+            raise ValueError("one GEMM call takes at most 256 tokens")
+        self.s, self.B, self.R, self.dev = s, B, R, torch.device(device)
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(11)
+        bf = lambda *sh: (torch.randn(*sh, generator=g, device=self.dev) * 0.5).to(torch.bfloat16)
+        w = lambda n, k: (torch.randn(n, k, generator=g, device=self.dev) * k ** -0.5).to(torch.bfloat16)
+        qkv_n = (s.Hq + 2 * s.Hkv) * s.D
+        first = {"qkv": w(qkv_n, s.hidden), "o": w(s.hidden, s.Hq * s.D), "gate_up": w(2 * s.mlp, s.hidden),
+                 "down": w(s.hidden, s.mlp), "Kpre": bf(s.Hkv, prefix, s.D), "Vpre": bf(s.Hkv, prefix, s.D),
+                 "Kpriv": bf(B, s.Hkv, private + R, s.D), "Vpriv": bf(B, s.Hkv, private + R, s.D)}
+        # the other layers hold copies: the values do not matter to the time, that each layer is its own memory does
+        self.layers = [first] + [{k: v.clone() for k, v in first.items()} for _ in range(s.layers - 1)]
+        self.lm_head = w(s.V, s.hidden)
+        self.priv_len = torch.full((B,), private + R, dtype=torch.int32, device=self.dev)
+        z = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16, device=self.dev)
+        self.h = bf(M, s.hidden)
+        self.qkv, self.attn, self.o, self.gu = z(M, qkv_n), z(B, R, s.Hq, s.D), z(M, s.hidden), z(M, 2 * s.mlp)
+        self.q_view = self.qkv.view(B, R, s.Hq + 2 * s.Hkv, s.D)[:, :, :s.Hq]
+        self.zt = z(B, R, s.V)
+        self.zd = bf(B, gamma, s.V) if gamma else None
+        self.draft = torch.zeros((B, gamma), dtype=torch.int32, device=self.dev) if gamma else None
+        self.u = torch.full((B, R), 0.5, dtype=torch.float32, device=self.dev)
+        self.accept_len = torch.zeros((B,), dtype=torch.int32, device=self.dev)
+        self.next_token = torch.zeros((B,), dtype=torch.int32, device=self.dev)
+        lib = binding.load()
+        gemm_ws = max(lib.skinny_gemm_workspace_bytes(M, n, k) for n, k in
+                      ((qkv_n, s.hidden), (s.hidden, s.Hq * s.D), (2 * s.mlp, s.hidden), (s.hidden, s.mlp), (s.V, s.hidden)))
+        ws = lambda n: torch.zeros(max(int(n), 256), dtype=torch.uint8, device=self.dev)
+        desc = binding.make_attn_desc(self.q_view, first["Kpre"], first["Kpriv"], self.attn)
+        self.ws_gemm = ws(gemm_ws)
+        self.ws_attn = ws(lib.verify_attention_workspace_bytes(ctypes.byref(desc)))
+        self.ws_accept = ws(lib.spec_accept_logits_workspace_bytes(B, gamma, s.V))
+        self.graph = None
+
+    def enqueue(self) -> None:
+        """One verify step of the whole stack on the current stream; allocates nothing."""
+        s, M = self.s, self.B * self.R
+        h = self.h
+        for L in self.layers:
+            binding.skinny_gemm(h, L["qkv"], out=self.qkv, workspace=self.ws_gemm)
+            binding.verify_attention(self.q_view, L["Kpre"], L["Vpre"], L["Kpriv"], L["Vpriv"], self.priv_len,
+                                     out=self.attn, workspace=self.ws_attn)
+            binding.skinny_gemm(self.attn.view(M, s.Hq * s.D), L["o"], out=self.o, workspace=self.ws_gemm)
+            binding.skinny_gemm(self.o, L["gate_up"], out=self.gu, workspace=self.ws_gemm)
+            binding.skinny_gemm(self.gu[:, :s.mlp], L["down"], out=self.o, workspace=self.ws_gemm)
+            h = self.o
+        binding.skinny_gemm(h, self.lm_head, out=self.zt.view(M, s.V), workspace=self.ws_gemm)
+        binding.spec_accept_logits(self.zt, self.zd, self.draft, self.u, accept_len=self.accept_len,
+                                   next_token=self.next_token, workspace=self.ws_accept)
+
+    def step_ms(self, reps: int = 5) -> float:
+        """Device milliseconds of one verify step: mean over `reps` replays of the captured step."""
+        if self.graph is None:
+            self.enqueue()  # once outside the capture: whatever is created lazily exists before it
+            torch.cuda.synchronize()
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph):
+                self.enqueue()
+        for _ in range(2):
+            self.graph.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            self.graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+
 def expected_tokens_per_step(alpha: float, gamma: int) -> float:
     """Tokens a branch emits per verify step when each draft is accepted with probability alpha:
     1 + alpha + ... + alpha^gamma (the accepted drafts plus the resampled or bonus token)."""
@@ -176,7 +261,22 @@ def main() -> int:
     ap.add_argument("--draft-ratio", type=float, default=0.1)
     ap.add_argument("--B-max", type=int, default=64)
     ap.add_argument("--gamma-max", type=int, default=7)
+    ap.add_argument("--full-model", metavar="B,GAMMA", action="append", default=[],
+                    help="also hold every layer of the shape on the GPU and time one verify step of the whole stack "
+                         "for this (B, gamma), against the sum of isolated kernel times the search uses")
     a = ap.parse_args()
+    for spec in a.full_model:
+        B, gamma = (int(x) for x in spec.split(","))
+        prefix, context = 512, 4096
+        private = max(gamma + 1, context // 2) - (gamma + 1)
+        fm = FullModel(SHAPES[a.shape], prefix, private, B, gamma)
+        measured = fm.step_ms()
+        del fm
+        torch.cuda.empty_cache()
+        modelled = StepTimer(SHAPES[a.shape], prefix, context, B, gamma).verify_step_ms(B, gamma, private)
+        print(json.dumps({"full_model": SHAPES[a.shape].name, "B": B, "gamma": gamma, "private_tokens": private,
+                          "step_ms_whole_stack_graph_replay": measured, "step_ms_sum_of_kernel_times": modelled["total"],
+                          "per_layer_ms_sum_of_kernel_times": modelled["layer"]}), flush=True)
     out = search(a.shape, a.budget_s, alpha=a.alpha, draft_ratio=a.draft_ratio, B_max=a.B_max, gamma_max=a.gamma_max,
                  verbose=True)
     print(json.dumps(out))

@@ -670,6 +670,30 @@ def test_greedy_search_on_measured_step_latencies(lotts):
     assert lm.expected_tokens_per_step(1.0, 3) == 4.0 and lm.expected_tokens_per_step(0.5, 0) == 1.0
 
 
+def test_whole_stack_verify_step_replays_what_it_ran_eagerly(lotts):
+    """Every layer of a tiny decoder shape resident, one verify step of the whole stack (projections, attention on
+    the strided Q columns, LM head, acceptance from logits) enqueued eagerly and then replayed from a captured
+    graph: the replay reproduces the eager results bit for bit and reports a device time."""
+    from paper_2505_19634_amd import latency_model as lm
+    shape = lm.ModelShape("tiny decoder", 2, 512, 8, 2, 64, 1024, 4096)
+    fm = lm.FullModel(shape, prefix=64, private=200, B=4, gamma=2)
+    fm.enqueue()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (fm.o, fm.zt, fm.accept_len, fm.next_token)]
+    # layer 0's QKV projection and the LM head against plain matrix products of the same bf16 inputs
+    ref = fm.h.float() @ fm.layers[0]["qkv"].float().t()
+    lotts.skinny_gemm(fm.h, fm.layers[0]["qkv"], out=fm.qkv, workspace=fm.ws_gemm)
+    assert torch.allclose(fm.qkv.float(), ref, rtol=2 ** -7, atol=1e-2)
+    assert torch.allclose(fm.zt.view(-1, shape.V).float(), fm.o.float() @ fm.lm_head.float().t(), rtol=2 ** -7, atol=1e-2)
+    for t in (fm.o, fm.zt):
+        t.zero_()
+    ms = fm.step_ms(reps=3)
+    got = (fm.o, fm.zt, fm.accept_len, fm.next_token)
+    assert all(torch.equal(a, b) for a, b in zip(got, want))
+    assert ms > 0.0 and bool(((fm.next_token >= 0) & (fm.next_token < shape.V)).all())
+    assert bool(((fm.accept_len >= 0) & (fm.accept_len <= 2)).all())
+
+
 def test_attention_strided_q_and_o(lotts, oracle):
     """Q and O handed over as views into larger tensors (extra heads and extra positions around them): only the
     strides change, the padding is never touched."""
