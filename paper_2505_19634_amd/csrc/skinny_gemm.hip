@@ -3,15 +3,12 @@
 // 64 GB of weights for the 32B model).  bf16 in, fp32 accumulate on the matrix cores, bf16 out.
 // HBM-bound on streaming W once: 2 * M flop per weight byte is far below the MFMA balance.
 //
-//   skinny_gemm_kernel<MT>  up to 64 tokens; grid (blocks of 128 weight rows, K splits).  Each of the 4 wavefronts owns 32
-//       weight rows and walks the K range in chunks of 128: the W tile (32 x 128, 8 KB) comes in with
-//       coalesced non-temporal 16-byte loads two chunks ahead, is staged through a wavefront-private LDS
-//       slab and read back as the MFMA A operand; the X chunk (up to 256 x 128) is fetched once per
-//       workgroup from the L2 into a double-buffered LDS tile shared by the 4 wavefronts (one barrier per
-//       chunk) and read as the B operand.  Y^T[n][m] accumulates in registers over the whole K range.
-//   skinny_gemm_stream_kernel<MT>  more than 64 tokens, or long K runs; grid (blocks of 256 weight rows, K splits):
-//       8 wavefronts with one row tile each (two wavefronts per SIMD); W and X both go from global memory straight
-//       into LDS stages of half a chunk, with no registers in between.
+//   skinny_gemm_stream_kernel<MT, RT, WAVES>  grid (blocks of 32 * WAVES weight rows, K splits).  Each wavefront
+//       owns an MFMA row tile of 32 weight rows and walks the K range in steps of half a chunk (64 k); W and X both go
+//       from global memory straight into LDS stages, with no registers in between; Y^T[n][m] accumulates in
+//       registers over the whole K range.  WAVES = 8 (256 weight rows, one workgroup per unit): long K runs and
+//       every launch with more than 64 tokens.  WAVES = 4 (128 weight rows, two workgroups per unit): up to 64 tokens
+//       on short K runs (QKV, O), where more, smaller workgroups keep every unit streaming.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -21,14 +18,10 @@ namespace lotts {
 typedef __bf16 g_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 g_bf16x4 __attribute__((ext_vector_type(4)));
 typedef float g_f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned g_u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGemmThreads = 256;
-constexpr int kGemmWaves = 4;
-constexpr int kGemmRows = 32;                         // weight rows per wavefront = M of the MFMA
-constexpr int kGemmBlockN = kGemmWaves * kGemmRows;   // weight rows per workgroup
+constexpr int kGemmRows = 32;               // weight rows per wavefront = M of the MFMA
+constexpr int kGemmBlockN = 4 * kGemmRows;  // weight rows of a four-wavefront workgroup; eight wavefronts cover twice that
 constexpr int kGemmChunk = 128;                       // K elements per chunk
-constexpr int kGemmRowBytes = kGemmChunk * 2 + 16;    // LDS row pitch: conflict-free 16-byte row reads
 constexpr int kGemmMaxM = 256;
 constexpr int kGemmMaxSplit = 32;
 
@@ -41,7 +34,7 @@ struct GemmParams {
 };
 
 struct GemmPlan {
-    int mt, stream, nblocks, ksplit;  // stream: skinny_gemm_stream_kernel (256 weight rows per workgroup)
+    int mt, stream, nblocks, ksplit;  // stream: eight wavefronts, 256 weight rows per workgroup; else four and 128
 };
 // K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
 // Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
@@ -62,10 +55,10 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     GemmPlan pl;
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
-    // The streaming kernel covers 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged in LDS
-    // serves twice the rows of the narrow kernel.  Up to 64 tokens it wins when its workgroups still get long runs
-    // of chunks (gate+up, down on the 32B-shaped layers) and loses on short ones (QKV, O); above 64 tokens the
-    // narrow kernel's registers do not hold the accumulators of two workgroups per unit, and it always runs.
+    // Eight wavefronts cover 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged in LDS
+    // serves twice the rows of the four-wavefront form.  Up to 64 tokens they win when the workgroups still get long
+    // runs of chunks (gate+up, down on the 32B-shaped layers) and lose on short ones (QKV, O); above 64 tokens two
+    // workgroups per unit do not fit (LDS stages, accumulators), and the eight-wavefront form always runs.
     const int nb_stream = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
     const int ks_stream = plan_ksplit(nb_stream, chunks, false);
     pl.stream = (pl.mt > 2 || chunks / ks_stream >= 16) ? 1 : 0;
@@ -79,124 +72,8 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     return pl;
 }
 
-template <int MT>
-__global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const GemmParams p) {
-    constexpr int XROWS = 32 * MT;
-    __shared__ __attribute__((aligned(16))) unsigned char xbuf[2][XROWS * kGemmRowBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char wslab_all[kGemmWaves][kGemmRows * kGemmRowBytes];
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
-    const int ln = lane & 31, hh = lane >> 5;
-    const int n0 = blockIdx.x * kGemmBlockN + wave * kGemmRows;
-    const int chunks = p.K / kGemmChunk;
-    const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
-    const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
-    unsigned char* wslab = wslab_all[wave];
-
-    // W tile: 8 load instructions, each covering 4 whole 256-byte row pieces
-    const int w_row = lane >> 4, w_ch = lane & 15;
-    // Two W chunks are in flight per wavefront (16 KB), in two register sets that take turns: a set is
-    // refilled with chunk c + 2 as soon as chunk c has been copied from it into the LDS slab.
-    g_u32x4 w_even[8], w_odd[8];
-    auto fetch_w = [&](int c, g_u32x4 (&dst)[8]) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int n = n0 + i * 4 + w_row;
-            n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
-            dst[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const g_u32x4*>(p.W + (long long)n * p.ldw + (long long)c * kGemmChunk + w_ch * 8));
-        }
-    };
-    // X chunk: XROWS rows x 16 pieces of 16 bytes, 2 * MT pieces per thread
-    g_u32x4 x_even[2 * MT], x_odd[2 * MT];
-    auto fetch_x = [&](int c, g_u32x4 (&xst)[2 * MT]) {
-#pragma unroll
-        for (int i = 0; i < 2 * MT; ++i) {
-            const int idx = tid + i * kGemmThreads;
-            int m = idx >> 4;
-            m = m < p.M ? m : p.M - 1;
-            xst[i] = *reinterpret_cast<const g_u32x4*>(p.X + (long long)m * p.ldx + (long long)c * kGemmChunk + (idx & 15) * 8);
-        }
-    };
-    g_f32x16 acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-
-    // One chunk.  Loads complete in issue order and every chunk's X piece is issued before its W piece,
-    // so the barrier (X staged by all four wavefronts) never waits for anybody's W data: each wavefront
-    // waits for its own W chunk after the barrier and the four drift apart by up to one chunk.
-    auto chunk = [&](int c, g_u32x4 (&w)[8], g_u32x4 (&xst)[2 * MT]) {
-        unsigned char* xb = xbuf[(c - c_lo) & 1];
-#pragma unroll
-        for (int i = 0; i < 2 * MT; ++i) {
-            const int idx = tid + i * kGemmThreads;
-            *reinterpret_cast<g_u32x4*>(xb + (idx >> 4) * kGemmRowBytes + (idx & 15) * 16) = xst[i];
-        }
-        __syncthreads();  // the X chunk is complete; the other buffer is free for chunk c + 1
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<g_u32x4*>(wslab + (i * 4 + w_row) * kGemmRowBytes + w_ch * 16) = w[i];
-        if (c + 2 < c_hi) {
-            fetch_x(c + 2, xst);
-            fetch_w(c + 2, w);
-        }
-        // Y^T[n][m] += sum_k W[n][k] X[m][k]   (A = W rows, B = X rows, 8 steps of 16 k); the fragments of
-        // step s + 1 are requested before the MFMAs of step s, so that LDS reads and matrix work overlap
-        auto frags = [&](int s, g_bf16x8& a, g_bf16x8 (&b)[MT]) {
-            a = *reinterpret_cast<const g_bf16x8*>(wslab + ln * kGemmRowBytes + (2 * s + hh) * 16);
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-                b[t] = *reinterpret_cast<const g_bf16x8*>(xb + (t * 32 + ln) * kGemmRowBytes + (2 * s + hh) * 16);
-        };
-        g_bf16x8 fa[2], fb[2][MT];
-        frags(0, fa[0], fb[0]);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            if (s + 1 < 8) frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1], fb[s & 1][t], acc[t], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    if (c_lo < c_hi) {
-        fetch_x(c_lo, x_even);
-        fetch_w(c_lo, w_even);
-    }
-    if (c_lo + 1 < c_hi) {
-        fetch_x(c_lo + 1, x_odd);
-        fetch_w(c_lo + 1, w_odd);
-    }
-    for (int c = c_lo; c < c_hi; c += 2) {
-        chunk(c, w_even, x_even);
-        if (c + 1 < c_hi) chunk(c + 1, w_odd, x_odd);
-    }
-    // register i of this lane: output row m = t * 32 + ln, column n = n0 + (i / 4) * 8 + hh * 4 + i % 4
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const int m = t * 32 + ln;
-        if (m >= p.M) continue;
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int n = n0 + q4 * 8 + hh * 4;
-            if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
-            if (p.ksplit == 1) {
-                g_bf16x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[t][q4 * 4 + e];
-                *reinterpret_cast<g_bf16x4*>(p.Y + (long long)m * p.ldy + n) = o;
-            } else {
-                *reinterpret_cast<float4*>(p.part + ((long long)blockIdx.y * p.M + m) * p.N + n) =
-                    make_float4(acc[t][q4 * 4 + 0], acc[t][q4 * 4 + 1], acc[t][q4 * 4 + 2], acc[t][q4 * 4 + 3]);
-            }
-        }
-    }
-}
-
-// Long K runs at any token count, and every launch with more than 64 tokens.  Eight wavefronts (two per SIMD),
-// 256 weight rows per workgroup, one workgroup per unit: each wavefront owns one MFMA row tile of 32 weight rows and
+// The kernel.  WAVES wavefronts (eight: two per SIMD, one workgroup per unit; four: two workgroups per unit),
+// 32 * WAVES weight rows per workgroup: each wavefront owns one MFMA row tile of 32 weight rows and
 // all M tokens -- or, for an even number of token tiles from 4 on (97..128, 161..192, 225..256 tokens), two
 // neighbouring wavefronts own two row tiles together and half of the token tiles each: a k step then reads
 // 2 + MT / 2 fragments for MT MFMAs instead of 1 + MT, and LDS reads are what bounds the loop at these token counts
@@ -220,22 +97,22 @@ __global__ __launch_bounds__(kGemmThreads, 2) void skinny_gemm_kernel(const Gemm
 // compiler does not know of the loads, the waits are written out too: before the barrier of a step, vmcnt(4) -- the
 // step's X transfers have landed, and with them the older W stage; only the 4 W transfers issued after them (the
 // next step's stage) may still be in flight -- or vmcnt(0) in the last step, after which nothing was issued.
-template <int MT, int RT>
-__global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const GemmParams p) {
+template <int MT, int RT, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave, 8 / WAVES) void skinny_gemm_stream_kernel(const GemmParams p) {
     static_assert(RT == 1 || (RT == 2 && MT % 2 == 0), "a pair of wavefronts splits the token tiles evenly");
     constexpr int TT = MT / RT;  // token tiles per wavefront
     constexpr int XROWS = 32 * MT;
     constexpr int XINSTR = XROWS / 8;
-    constexpr int XI = (XINSTR + 7) / 8;
+    constexpr int XI = (XINSTR + WAVES - 1) / WAVES;
     constexpr int kStageRow = 128;
     constexpr int XSTAGE = XROWS * kStageRow, WSTAGE = 32 * kStageRow;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * XSTAGE + 8 * 3 * WSTAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * XSTAGE + WAVES * 3 * WSTAGE];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
     const int ln = lane & 31, hh = lane >> 5;
     // RT = 1: wavefront w owns row tile w and all tokens.  RT = 2: wavefronts 2j and 2j + 1 own row tiles 2j and
     // 2j + 1 together, each half of the token tiles, and share the W stages of their 64 rows.
     const int grp = RT == 1 ? wave : wave >> 1, th = RT == 1 ? 0 : wave & 1;
-    const int n0 = blockIdx.x * 256 + grp * (32 * RT);
+    const int n0 = blockIdx.x * (kGemmRows * WAVES) + grp * (kGemmRows * RT);
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
@@ -251,7 +128,7 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
     const __bf16* w_src[4];
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
-        const int r = (wave + i * 8) * 8 + l_row;
+        const int r = (wave + i * WAVES) * 8 + l_row;
         const int m = r < p.M ? r : p.M - 1;
         x_src[i] = p.X + (long long)m * p.ldx + (long long)c_lo * kGemmChunk + (l_slot ^ ((r >> 1) & 7)) * 8;
     }
@@ -268,7 +145,7 @@ __global__ __launch_bounds__(8 * kWave, 1) void skinny_gemm_stream_kernel(const 
         unsigned char* stage = xs + (g & 1) * XSTAGE;
 #pragma unroll
         for (int i = 0; i < XI; ++i) {
-            const int j = wave + i * 8;
+            const int j = wave + i * WAVES;
             if (j < XINSTR) {
                 const unsigned lds_base = __builtin_amdgcn_readfirstlane(
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)(stage + j * 8 * kStageRow));
@@ -418,22 +295,22 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit;
     p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid(pl.nblocks, pl.ksplit), block(kGemmThreads), block8(8 * kWave);
+    const dim3 grid(pl.nblocks, pl.ksplit), block4(4 * kWave), block8(8 * kWave);
     if (pl.stream) {
         switch (pl.mt) {
-            case 1: LOTTS_LAUNCH((skinny_gemm_stream_kernel<1, 1>), grid, block8, s, p); break;
-            case 2: LOTTS_LAUNCH((skinny_gemm_stream_kernel<2, 1>), grid, block8, s, p); break;
-            case 3: LOTTS_LAUNCH((skinny_gemm_stream_kernel<3, 1>), grid, block8, s, p); break;
-            case 4: LOTTS_LAUNCH((skinny_gemm_stream_kernel<4, 2>), grid, block8, s, p); break;
-            case 5: LOTTS_LAUNCH((skinny_gemm_stream_kernel<5, 1>), grid, block8, s, p); break;
-            case 6: LOTTS_LAUNCH((skinny_gemm_stream_kernel<6, 2>), grid, block8, s, p); break;
-            case 7: LOTTS_LAUNCH((skinny_gemm_stream_kernel<7, 1>), grid, block8, s, p); break;
-            default: LOTTS_LAUNCH((skinny_gemm_stream_kernel<8, 2>), grid, block8, s, p); break;
+            case 1: LOTTS_LAUNCH((skinny_gemm_stream_kernel<1, 1, 8>), grid, block8, s, p); break;
+            case 2: LOTTS_LAUNCH((skinny_gemm_stream_kernel<2, 1, 8>), grid, block8, s, p); break;
+            case 3: LOTTS_LAUNCH((skinny_gemm_stream_kernel<3, 1, 8>), grid, block8, s, p); break;
+            case 4: LOTTS_LAUNCH((skinny_gemm_stream_kernel<4, 2, 8>), grid, block8, s, p); break;
+            case 5: LOTTS_LAUNCH((skinny_gemm_stream_kernel<5, 1, 8>), grid, block8, s, p); break;
+            case 6: LOTTS_LAUNCH((skinny_gemm_stream_kernel<6, 2, 8>), grid, block8, s, p); break;
+            case 7: LOTTS_LAUNCH((skinny_gemm_stream_kernel<7, 1, 8>), grid, block8, s, p); break;
+            default: LOTTS_LAUNCH((skinny_gemm_stream_kernel<8, 2, 8>), grid, block8, s, p); break;
         }
     } else if (pl.mt == 1) {
-        LOTTS_LAUNCH(skinny_gemm_kernel<1>, grid, block, s, p);
+        LOTTS_LAUNCH((skinny_gemm_stream_kernel<1, 1, 4>), grid, block4, s, p);
     } else {
-        LOTTS_LAUNCH(skinny_gemm_kernel<2>, grid, block, s, p);
+        LOTTS_LAUNCH((skinny_gemm_stream_kernel<2, 1, 4>), grid, block4, s, p);
     }
     int rc = check_launch();
     if (rc != LOTTS_OK || pl.ksplit == 1) return rc;
