@@ -7,8 +7,8 @@
 //       owns an MFMA row tile of 32 weight rows and walks the K range in steps of half a chunk (64 k); W and X both go
 //       from global memory straight into LDS stages, with no registers in between; Y^T[n][m] accumulates in
 //       registers over the whole K range.  WAVES = 8 (256 weight rows, one workgroup per unit): long K runs and
-//       every launch with more than 64 tokens.  WAVES = 4 (128 weight rows, two workgroups per unit): up to 64 tokens
-//       on short K runs (QKV, O), where more, smaller workgroups keep every unit streaming.
+//       every launch with more than 128 tokens.  WAVES = 4 (128 weight rows, two workgroups per unit): up to 128
+//       tokens on short K runs (QKV, O), where more, smaller workgroups keep every unit streaming.
 //   skinny_gemm_reduce_kernel  only when K is split across workgroups (few weight rows): sums the fp32
 //       partials in a fixed order and converts.
 #include "lotts_common.h"
@@ -56,12 +56,13 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     pl.mt = (M + 31) / 32;
     const int chunks = K / kGemmChunk;
     // Eight wavefronts cover 256 weight rows per workgroup, one workgroup per unit, so an X chunk staged in LDS
-    // serves twice the rows of the four-wavefront form.  Up to 64 tokens they win when the workgroups still get long
-    // runs of chunks (gate+up, down on the 32B-shaped layers) and lose on short ones (QKV, O); above 64 tokens two
-    // workgroups per unit do not fit (LDS stages, accumulators), and the eight-wavefront form always runs.
+    // serves twice the rows of the four-wavefront form.  Up to 128 tokens they win when the workgroups still get long
+    // runs of chunks (gate+up, down on the 32B-shaped layers) and lose on short ones (QKV, O: the four-wavefront form
+    // splits K less, so fewer fp32 partials are written and added up); above 128 tokens two workgroups per unit do
+    // not fit (LDS stages, accumulators), and the eight-wavefront form always runs.
     const int nb_stream = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
     const int ks_stream = plan_ksplit(nb_stream, chunks, false);
-    pl.stream = (pl.mt > 2 || chunks / ks_stream >= 16) ? 1 : 0;
+    pl.stream = (pl.mt > 4 || chunks / ks_stream >= 16) ? 1 : 0;
     if (pl.stream) {
         pl.nblocks = nb_stream;
         pl.ksplit = ks_stream;
@@ -309,8 +310,12 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
         }
     } else if (pl.mt == 1) {
         LOTTS_LAUNCH((skinny_gemm_stream_kernel<1, 1, 4>), grid, block4, s, p);
-    } else {
+    } else if (pl.mt == 2) {
         LOTTS_LAUNCH((skinny_gemm_stream_kernel<2, 1, 4>), grid, block4, s, p);
+    } else if (pl.mt == 3) {
+        LOTTS_LAUNCH((skinny_gemm_stream_kernel<3, 1, 4>), grid, block4, s, p);
+    } else {
+        LOTTS_LAUNCH((skinny_gemm_stream_kernel<4, 2, 4>), grid, block4, s, p);
     }
     int rc = check_launch();
     if (rc != LOTTS_OK || pl.ksplit == 1) return rc;

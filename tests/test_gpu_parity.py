@@ -516,6 +516,7 @@ def test_confidence_vote(lotts, oracle, N, B, T):
 @pytest.mark.parametrize("M,N,K", [
     (64, 512, 1024), (40, 136, 256), (5, 8, 128), (1, 1000, 384), (128, 256, 512), (97, 264, 640),
     (129, 520, 384), (192, 2048, 2048), (256, 640, 1280), (231, 136, 128),   # 5, 6 and 8 token tiles
+    (80, 1032, 768),        # three token tiles on the four-wavefront form, the last one ragged
     (170, 1032, 768),       # pairs of wavefronts with three token tiles each, the last one ragged; 8 weight rows in the last block
     (192, 11008, 2048),     # 3B-shaped MLP up projection for B = 64 branches, k = 2
     (64, 7168, 5120),       # 32B-shaped QKV projection for B * (k + 1) = 64 tokens (K split over workgroups)
