@@ -20,8 +20,8 @@ typedef __bf16 g_bf16x4 __attribute__((ext_vector_type(4)));
 typedef float g_f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kGemmRows = 32;               // weight rows per wavefront = M of the MFMA
-constexpr int kGemmBlockN = 4 * kGemmRows;  // weight rows of a four-wavefront workgroup; eight wavefronts cover twice that
-constexpr int kGemmChunk = 128;                       // K elements per chunk
+constexpr int kGemmBlockN = 4 * kGemmRows;  // weight rows of a four-wavefront workgroup; eight cover twice that
+constexpr int kGemmChunk = 128;             // K elements per chunk
 constexpr int kGemmMaxM = 256;
 constexpr int kGemmMaxSplit = 32;
 
