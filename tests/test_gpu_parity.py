@@ -548,7 +548,7 @@ def test_skinny_gemm(lotts, oracle, M, N, K):
     assert np.linalg.norm(y - ref) / np.linalg.norm(ref) <= 3e-3
 
 
-@pytest.mark.parametrize("M", [48, 256])    # 256 tokens take the kernel that brings X in by global-to-LDS loads
+@pytest.mark.parametrize("M", [48, 256])    # one row tile per wavefront; pairs of wavefronts
 def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle, M):
     g = S.rng_for(7, 31, salt=M)
     N, K = 640, 768
@@ -561,6 +561,33 @@ def test_skinny_gemm_strided_rows_and_determinism(lotts, oracle, M):
     assert torch.equal(Y1, Y2) and float(out[:, N:].abs().sum()) == 0.0
     ref = oracle.skinny_gemm(X.contiguous().view(torch.uint16).cpu().numpy(), W.contiguous().view(torch.uint16).cpu().numpy())
     assert np.linalg.norm(Y1.float().cpu().numpy() - ref) / np.linalg.norm(ref) <= 3e-3
+
+
+def test_skinny_gemm_weights_beyond_4_gib(lotts, oracle):
+    """A weight matrix of 4.56 GB: the rows past the 4 GiB mark are reached through 64-bit addresses.  The oracle
+    checks the first and the last 256 weight rows (the whole product would take it minutes); the rows around the
+    2 GiB and 4 GiB marks are compared with a plain matrix product."""
+    M, N, K = 40, 278528, 8192
+    g = torch.Generator(device=DEV)
+    g.manual_seed(41)
+    W = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    for r0 in range(0, N, 32768):                        # generated in pieces: no fp32 copy of the whole matrix
+        r1 = min(N, r0 + 32768)
+        W[r0:r1] = (torch.randn((r1 - r0, K), generator=g, device=DEV) * K ** -0.5).to(torch.bfloat16)
+    assert W.numel() * 2 > (1 << 32)
+    X = torch.randn((M, K), generator=g, device=DEV).to(torch.bfloat16)
+    Y = lotts.skinny_gemm(X, W)
+    torch.cuda.synchronize()
+    xb = X.view(torch.uint16).cpu().numpy()
+    for lo, hi in ((0, 256), (N - 256, N)):
+        ref = oracle.skinny_gemm(xb, W[lo:hi].contiguous().view(torch.uint16).cpu().numpy())
+        y = Y[:, lo:hi].float().cpu().numpy().astype(np.float64)
+        assert (np.abs(y - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-3).all(), (lo, np.abs(y - ref).max())
+    # rows around the 2 GiB mark (where a signed 32-bit byte offset would wrap), around the 4 GiB mark and at the end,
+    # against a plain matrix product of the same rows
+    for lo in ((1 << 31) // (2 * K) - 1024, (1 << 32) // (2 * K) - 1024, N - 2048):
+        want = X.float() @ W[lo:lo + 2048].float().t()
+        assert torch.allclose(Y[:, lo:lo + 2048].float(), want, rtol=2 ** -7, atol=1e-2), lo
 
 
 # ---------------------------------------------------------------------------- kernel timer
