@@ -722,6 +722,34 @@ def test_whole_stack_verify_step_replays_what_it_ran_eagerly(lotts):
     assert bool(((fm.accept_len >= 0) & (fm.accept_len <= 2)).all())
 
 
+def test_attention_private_caches_beyond_4_gib(lotts, oracle):
+    """Private K and V of 5.7 GB each (20 branches of 139264 tokens, ragged lengths): the branches whose caches lie
+    around the 2 GiB and 4 GiB marks and the last one are checked against the oracle, one branch at a time."""
+    B, Hq, Hkv, D, k, L = 20, 8, 8, 128, 1, 139264
+    g = torch.Generator(device=DEV)
+    g.manual_seed(43)
+    mk = lambda *sh: (torch.randn(*sh, generator=g, device=DEV) * 0.5).to(torch.bfloat16)
+    Kpriv = torch.empty((B, Hkv, L, D), dtype=torch.bfloat16, device=DEV)
+    Vpriv = torch.empty((B, Hkv, L, D), dtype=torch.bfloat16, device=DEV)
+    for b in range(B):                                   # in pieces: no fp32 copy of a whole cache
+        Kpriv[b] = mk(Hkv, L, D)
+        Vpriv[b] = mk(Hkv, L, D)
+    assert Kpriv.numel() * 2 > (1 << 32)
+    Q = mk(B, k + 1, Hq, D)
+    priv_len = torch.tensor([L - 37 * b for b in range(B)], dtype=torch.int32, device=DEV)
+    O, lse = lotts.verify_attention(Q, None, None, Kpriv, Vpriv, priv_len, return_lse=True)
+    torch.cuda.synchronize()
+    bits = lambda t: t.contiguous().view(torch.uint16).cpu().numpy()
+    tol = TOL["bf16"]
+    for b in (0, 7, 15, B - 1):                          # 285 MB per branch: 7 holds the 2 GiB mark, 15 the 4 GiB mark
+        Oref, lref = oracle.verify_attention(bits(Q[b:b + 1]), None, None, bits(Kpriv[b:b + 1]), bits(Vpriv[b:b + 1]),
+                                             priv_len[b:b + 1].cpu().numpy())
+        e_abs, e_fro, _ = attn_errors(O[b:b + 1], Oref)
+        print("  branch %d: max-abs %.3g  fro-rel %.3g" % (b, e_abs, e_fro), flush=True)
+        assert e_abs <= tol["abs"] and e_fro <= tol["fro_band"], b
+        assert np.abs(lse[b:b + 1].cpu().numpy().astype(np.float64) - lref).max() <= tol["lse"], b
+
+
 def test_attention_strided_q_and_o(lotts, oracle):
     """Q and O handed over as views into larger tensors (extra heads and extra positions around them): only the
     strides change, the padding is never touched."""
