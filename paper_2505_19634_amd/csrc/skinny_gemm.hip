@@ -30,11 +30,12 @@ struct GemmParams {
     __bf16* Y;
     float* part;  // [ksplit][M][N] fp32 when ksplit > 1
     int M, N, K, ksplit;
+    int rows;  // weight rows a wavefront owns: 32, or fewer (a multiple of 4) when that fills the chip better
     long long ldx, ldw, ldy;
 };
 
 struct GemmPlan {
-    int mt, stream, nblocks, ksplit;  // stream: eight wavefronts, 256 weight rows per workgroup; else four and 128
+    int mt, stream, nblocks, ksplit, rows;  // rows: weight rows per wavefront; stream: eight wavefronts, 256 weight rows per workgroup; else four and 128
 };
 // K split for `nblocks` blocks of weight rows.  Few blocks: split K so that the launch fills the chip.
 // Measured on the 32B-shaped layers: a workgroup count just above the number of compute units is the
@@ -60,13 +61,28 @@ static inline GemmPlan plan_gemm(int M, int N, int K) {
     // runs of chunks (gate+up, down on the 32B-shaped layers) and lose on short ones (QKV, O: the four-wavefront form
     // splits K less, so fewer fp32 partials are written and added up); above 128 tokens two workgroups per unit do
     // not fit (LDS stages, accumulators), and the eight-wavefront form always runs.
-    const int nb_stream = (N + 2 * kGemmBlockN - 1) / (2 * kGemmBlockN);
-    const int ks_stream = plan_ksplit(nb_stream, chunks, false);
+    pl.rows = kGemmRows;
+    int nb_stream = (N + 8 * kGemmRows - 1) / (8 * kGemmRows);
+    int ks_stream = plan_ksplit(nb_stream, chunks, false);
+    if (pl.mt <= 2) {
+        // Up to 64 tokens the launch is HBM-bound and what counts is how many units stream: with 28 weight rows per
+        // wavefront instead of 32 the 55296 rows of the 32B shape's gate+up make 247 workgroups instead of 216, and
+        // the LM head's last round of workgroups is fuller (measured 1..2 % and 2..7 % faster; with more tokens the
+        // padded MFMA rows cost more than the idle units).  Taken when it fills the last round visibly better.
+        const int nb28 = (N + 8 * 28 - 1) / (8 * 28), ks28 = plan_ksplit(nb28, chunks, false);
+        auto fill = [](int wgs) { return (double)wgs / (double)(((wgs + kNumCU - 1) / kNumCU) * kNumCU); };
+        if (fill(nb28 * ks28) > fill(nb_stream * ks_stream) + 0.03) {
+            pl.rows = 28;
+            nb_stream = nb28;
+            ks_stream = ks28;
+        }
+    }
     pl.stream = (pl.mt > 4 || chunks / ks_stream >= 16) ? 1 : 0;
     if (pl.stream) {
         pl.nblocks = nb_stream;
         pl.ksplit = ks_stream;
     } else {
+        pl.rows = kGemmRows;
         pl.nblocks = (N + kGemmBlockN - 1) / kGemmBlockN;
         pl.ksplit = plan_ksplit(pl.nblocks, chunks, true);
     }
@@ -113,7 +129,7 @@ __global__ __launch_bounds__(WAVES * kWave, 8 / WAVES) void skinny_gemm_stream_k
     // RT = 1: wavefront w owns row tile w and all tokens.  RT = 2: wavefronts 2j and 2j + 1 own row tiles 2j and
     // 2j + 1 together, each half of the token tiles, and share the W stages of their 64 rows.
     const int grp = RT == 1 ? wave : wave >> 1, th = RT == 1 ? 0 : wave & 1;
-    const int n0 = blockIdx.x * (kGemmRows * WAVES) + grp * (kGemmRows * RT);
+    const int n0 = blockIdx.x * (p.rows * WAVES) + grp * (p.rows * RT);  // pairs always own 2 x 32 rows
     const int chunks = p.K / kGemmChunk;
     const int c_lo = (int)((long long)blockIdx.y * chunks / p.ksplit);
     const int c_hi = (int)((long long)(blockIdx.y + 1) * chunks / p.ksplit);
@@ -136,7 +152,7 @@ __global__ __launch_bounds__(WAVES * kWave, 8 / WAVES) void skinny_gemm_stream_k
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = th * 32 + i * 8 + l_row;  // of a pair, each wavefront brings in 32 of the 64 rows
-        int n = n0 + r;
+        int n = n0 + (RT == 1 && r >= p.rows ? p.rows - 1 : r);  // a short tile re-reads its last row
         n = n < p.N ? n : p.N - 1;  // rows past the end re-read the last row; never stored
         w_src[i] = p.W + (long long)n * p.ldw + (long long)c_lo * kGemmChunk + (l_slot ^ ((r >> 1) & 7)) * 8;
     }
@@ -230,6 +246,7 @@ __global__ __launch_bounds__(WAVES * kWave, 8 / WAVES) void skinny_gemm_stream_k
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const int n = n0 + r * 32 + q4 * 8 + hh * 4;
+                if (RT == 1 && q4 * 8 + hh * 4 >= p.rows) continue;  // beyond a short tile (rows is a multiple of 4)
                 if (n >= p.N) continue;  // N is a multiple of 8: the 4 columns are in or out together
                 if (p.ksplit == 1) {
                     g_bf16x4 o;
@@ -293,7 +310,7 @@ extern "C" int skinny_gemm(int32_t M, int32_t N, int32_t K, const void* X, int64
     p.W = static_cast<const __bf16*>(W);
     p.Y = static_cast<__bf16*>(Y);
     p.part = static_cast<float*>(workspace);
-    p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit;
+    p.M = M; p.N = N; p.K = K; p.ksplit = pl.ksplit; p.rows = pl.rows;
     p.ldx = ldx; p.ldw = ldw; p.ldy = ldy;
     hipStream_t s = (hipStream_t)stream;
     const dim3 grid(pl.nblocks, pl.ksplit), block4(4 * kWave), block8(8 * kWave);
