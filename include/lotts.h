@@ -222,6 +222,27 @@ int confidence_vote(int32_t N, int32_t B, int32_t T, const int32_t *answers, con
                     const int32_t *conf_len, int32_t weight_mode, int32_t select_mode, int32_t *winner,
                     float *winner_score, void *stream);
 
+/*
+ * kv_append -- put the K and V rows of the k + 1 new tokens of every branch at the tail of that
+ * branch's private cache, where verify_attention expects them (Section 2: the target verifies the
+ * drafted tokens in one parallel forward, so their keys and values join the cache before the
+ * attention of that forward; together with the length roll-back of spec_accept_logits this is the
+ * cache side of one speculative step).
+ *   Kpriv[b][h][priv_len[b] - (k + 1) + r][:] = Knew[b][r][h][:]   for r = 0 .. k; V likewise
+ *   Knew, Vnew: [B][k+1][Hkv][D] views (element strides new_stride_b / _r / _h, D contiguous), e.g. the K
+ *       and V columns of a QKV projection's output; V uses the same strides as K
+ *   Kpriv, Vpriv: [B][Hkv][Lmax][D] in/out (element strides priv_stride_b / _h / _t, as in lotts_attn_desc)
+ *   priv_len [B] int32 (device): private tokens of branch b INCLUDING the k + 1 new ones; positions
+ *       outside [0, Lmax) are skipped (a violated contract never writes out of bounds)
+ *   dtype: LOTTS_BF16 or LOTTS_F32, of all four buffers; a row of D elements is a multiple of 16
+ *       bytes, and all pointers and strides are 16-byte aligned
+ * A plain copy: bit-exact; nothing else in the caches is touched.
+ */
+int kv_append(int32_t B, int32_t k, int32_t Hkv, int32_t D, lotts_dtype dtype, const void *Knew, const void *Vnew,
+              int64_t new_stride_b, int64_t new_stride_r, int64_t new_stride_h, void *Kpriv, void *Vpriv,
+              int64_t priv_stride_b, int64_t priv_stride_h, int64_t priv_stride_t, int32_t Lmax,
+              const int32_t *priv_len, void *stream);
+
 /* Bytes of workspace skinny_gemm needs (0 if the sizes are invalid). */
 size_t skinny_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
 

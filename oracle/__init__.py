@@ -6,5 +6,5 @@ lotts_oracle.c) and exposes numpy wrappers with the same three names as the GPU 
 It imports nothing from the HIP package.
 """
 from .oracle import (build, verify_attention, spec_accept, majority_vote,  # noqa: F401
-                     spec_accept_logits, logit_weights, confidence_vote, skinny_gemm, n_threads,
+                     spec_accept_logits, logit_weights, confidence_vote, skinny_gemm, kv_append, n_threads,
                      set_threads)

@@ -499,3 +499,31 @@ int oracle_skinny_gemm(int M, int N, int K, int dtype, const void *X, const void
         }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * kv_append: the K and V rows of the k + 1 new tokens of every branch are written at the tail of
+ * the branch's private cache, positions priv_len[b] - (k + 1) .. priv_len[b] - 1 (Section 2: the
+ * drafted tokens are verified in one parallel forward, so their keys and values are in the cache
+ * that forward's attention reads).  Dense layouts: Knew, Vnew [B][k+1][Hkv][D];
+ * Kpriv, Vpriv [B][Hkv][Lmax][D]; es = bytes per element.  Positions outside [0, Lmax) are skipped.
+ * ------------------------------------------------------------------------------------------- */
+int oracle_kv_append(int B, int k, int Hkv, int D, int Lmax, int es, const void *Knew, const void *Vnew, void *Kpriv,
+                     void *Vpriv, const int32_t *priv_len)
+{
+    if (B < 1 || k < 0 || Hkv < 1 || D < 1 || Lmax < 1 || (es != 2 && es != 4)) return -2;
+    if (!Knew || !Vnew || !Kpriv || !Vpriv || !priv_len) return -1;
+    const int R = k + 1;
+    const size_t row = (size_t)D * (size_t)es;
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < R; ++r) {
+            const int64_t t = (int64_t)priv_len[b] - R + r;
+            if (t < 0 || t >= Lmax) continue;
+            for (int h = 0; h < Hkv; ++h) {
+                const size_t src = (((size_t)b * R + r) * Hkv + h) * row;
+                const size_t dst = (((size_t)b * Hkv + h) * Lmax + (size_t)t) * row;
+                memcpy((char *)Kpriv + dst, (const char *)Knew + src, row);
+                memcpy((char *)Vpriv + dst, (const char *)Vnew + src, row);
+            }
+        }
+    return 0;
+}

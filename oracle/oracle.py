@@ -41,6 +41,8 @@ def _bind(lib):
     lib.oracle_spec_accept_logits.argtypes = [c_int] * 3 + [vp, vp, c_int, ctypes.c_float] + [vp] * 5
     lib.oracle_skinny_gemm.restype = c_int
     lib.oracle_skinny_gemm.argtypes = [c_int] * 4 + [vp] * 3
+    lib.oracle_kv_append.restype = c_int
+    lib.oracle_kv_append.argtypes = [c_int] * 6 + [vp] * 5
     lib.oracle_confidence_vote.restype = c_int
     lib.oracle_confidence_vote.argtypes = [c_int] * 3 + [vp] * 3 + [c_int] * 2 + [vp] * 2
     return lib
@@ -197,3 +199,19 @@ def skinny_gemm(X, W):
     if rc != 0:
         raise ValueError("oracle_skinny_gemm rejected the call (rc=%d)" % rc)
     return Y
+
+
+def kv_append(Knew, Vnew, Kpriv, Vpriv, priv_len):
+    """Returns copies of Kpriv, Vpriv [B][Hkv][Lmax][D] with the rows Knew, Vnew [B][k+1][Hkv][D] of the new tokens
+    written at positions priv_len[b] - (k+1) .. priv_len[b] - 1 (float32, or uint16 bf16 bit patterns)."""
+    Knew, Vnew = np.ascontiguousarray(Knew), np.ascontiguousarray(Vnew)
+    Kout, Vout = np.array(Kpriv, copy=True, order="C"), np.array(Vpriv, copy=True, order="C")
+    B, R, Hkv, D = Knew.shape
+    assert Vnew.shape == Knew.shape and Kout.shape == Vout.shape and Kout.shape[:2] == (B, Hkv) and Kout.shape[3] == D
+    assert Knew.dtype == Vnew.dtype == Kout.dtype == Vout.dtype and Knew.dtype in (np.float32, np.uint16)
+    priv_len = np.ascontiguousarray(priv_len, dtype=np.int32)
+    rc = _load().oracle_kv_append(B, R - 1, Hkv, D, Kout.shape[2], Knew.dtype.itemsize, _ptr(Knew), _ptr(Vnew),
+                                  _ptr(Kout), _ptr(Vout), _ptr(priv_len))
+    if rc != 0:
+        raise ValueError("oracle_kv_append rejected the call (rc=%d)" % rc)
+    return Kout, Vout

@@ -18,7 +18,7 @@ LOTTS_F32, LOTTS_BF16 = 0, 1
 
 EXPORTS = ("lotts_strerror", "verify_attention_workspace_bytes", "verify_attention", "verify_attention_noalloc",
            "spec_accept_workspace_bytes", "spec_accept", "spec_accept_logits_workspace_bytes", "spec_accept_logits",
-           "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "greedy_search",
+           "majority_vote", "confidence_vote", "skinny_gemm_workspace_bytes", "skinny_gemm", "kv_append", "greedy_search",
            "lotts_timer_start", "lotts_timer_pause", "lotts_timer_stop")
 
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
         lib.skinny_gemm_workspace_bytes.argtypes = [i32, i32, i32]
         lib.skinny_gemm.restype = ctypes.c_int
         lib.skinny_gemm.argtypes = [i32, i32, i32, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, sz, vp]
+        lib.kv_append.restype = ctypes.c_int
+        lib.kv_append.argtypes = [i32, i32, i32, i32, i32, vp, vp] + [ctypes.c_int64] * 3 + [vp, vp] + [ctypes.c_int64] * 3 + [i32, vp, vp]
         lib.greedy_search.restype = ctypes.c_int
         lib.greedy_search.argtypes = [TTS_TASK_FN, vp, ctypes.c_double, i32, i32, ctypes.POINTER(ctypes.c_int32),
                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double),
@@ -370,6 +372,35 @@ def skinny_gemm(X: torch.Tensor, W: torch.Tensor, *, out: Optional[torch.Tensor]
     if rc != 0:
         raise LottsError(rc, "skinny_gemm")
     return out
+
+
+def kv_append(Knew: torch.Tensor, Vnew: torch.Tensor, Kpriv: torch.Tensor, Vpriv: torch.Tensor, priv_len: torch.Tensor, *,
+              stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Knew/Vnew [B][k+1][Hkv][D] (views are fine: only D has to be contiguous, V with K's strides) go to positions
+    priv_len[b] - (k+1) .. priv_len[b] - 1 of Kpriv/Vpriv [B][Hkv][Lmax][D] (in place)."""
+    lib = load()
+    if not Kpriv.is_cuda:
+        raise ValueError("kv_append runs on the GPU only")
+    if Knew.dtype == torch.bfloat16:
+        dt = LOTTS_BF16
+    elif Knew.dtype == torch.float32:
+        dt = LOTTS_F32
+    else:
+        raise TypeError("K and V must be bfloat16 or float32")
+    if not (Vnew.dtype == Kpriv.dtype == Vpriv.dtype == Knew.dtype):
+        raise TypeError("all four buffers share one dtype")
+    B, R, Hkv, D = Knew.shape
+    if (tuple(Vnew.shape) != (B, R, Hkv, D) or Kpriv.shape[0] != B or Kpriv.shape[1] != Hkv or Kpriv.shape[3] != D or
+            Vpriv.shape != Kpriv.shape or Vnew.stride() != Knew.stride() or Vpriv.stride() != Kpriv.stride() or
+            Knew.stride(3) != 1 or Kpriv.stride(3) != 1):
+        raise ValueError("Knew/Vnew [B][k+1][Hkv][D] and Kpriv/Vpriv [B][Hkv][Lmax][D] with shared strides, D contiguous")
+    if priv_len.dtype != torch.int32 or tuple(priv_len.shape) != (B,):
+        raise TypeError("priv_len must be int32 [B]")
+    rc = lib.kv_append(B, R - 1, Hkv, D, dt, _ptr(Knew), _ptr(Vnew), Knew.stride(0), Knew.stride(1), Knew.stride(2),
+                       _ptr(Kpriv), _ptr(Vpriv), Kpriv.stride(0), Kpriv.stride(1), Kpriv.stride(2), Kpriv.shape[2],
+                       _ptr(priv_len), _stream_handle(stream))
+    if rc != 0:
+        raise LottsError(rc, "kv_append")
 
 
 class kernel_timer:

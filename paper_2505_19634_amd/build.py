@@ -11,7 +11,7 @@ LIB = os.path.join(_HERE, "liblotts.so")
 CALIB = os.path.join(_HERE, "calib_copy")
 PROBE = os.path.join(_HERE, "libread_probe.so")
 SOURCES = ["verify_attention.hip", "spec_accept.hip", "spec_accept_logits.hip", "majority_vote.hip",
-           "confidence_vote.hip", "skinny_gemm.hip", "kernel_timer.hip", "greedy_search.cpp"]
+           "confidence_vote.hip", "skinny_gemm.hip", "kv_append.hip", "kernel_timer.hip", "greedy_search.cpp"]
 
 
 def build(verbose: bool = False) -> str:

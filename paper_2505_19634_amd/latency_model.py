@@ -9,10 +9,10 @@ search is exercised end to end on real MI355X latencies.  Nothing here is one of
 experiments.
 
 Verify step of the target model for B branches and gamma drafts (M = B * (gamma + 1) new tokens):
-per layer QKV projection, attention, O projection, gate+up and down projections (skinny_gemm and
-verify_attention, one layer's buffers timed and multiplied by the layer count), then the LM head and
-the acceptance from logits.  Norms, rotary embedding, activation and KV append are not modelled (they
-are outside this library); the draft model's gamma sequential steps cost `draft_ratio` times a
+per layer QKV projection, append of the new K and V rows to the caches, attention, O projection, gate+up
+and down projections (skinny_gemm, kv_append and verify_attention, one layer's buffers timed and
+multiplied by the layer count), then the LM head and the acceptance from logits.  Norms, rotary
+embedding and activation are not modelled (they are outside this library); the draft model's gamma sequential steps cost `draft_ratio` times a
 one-token step of the target each (an assumption: a draft model a tenth of the target's size).
 
     python -m paper_2505_19634_amd.latency_model --shape 3B --budget-s 4
@@ -101,6 +101,9 @@ class StepTimer:
         pl = torch.full((B,), private + R, dtype=torch.int32, device=self.dev)
         args = (Q, self.Kpre, self.Vpre, self.Kpriv[:B], self.Vpriv[:B], pl)
         layer += self._timed(lambda: binding.verify_attention(*args))
+        heads = torch.zeros((B, R, s.Hq + 2 * s.Hkv, s.D), dtype=torch.bfloat16, device=self.dev)
+        layer += self._timed(lambda: binding.kv_append(heads[:, :, s.Hq:s.Hq + s.Hkv], heads[:, :, s.Hq + s.Hkv:],
+                                                       self.Kpriv[:B], self.Vpriv[:B], pl))
         head = self._gemm_ms(M, self.W["lm_head"])
         zt = torch.zeros((B, R, s.V), dtype=torch.bfloat16, device=self.dev)
         zd = torch.zeros((B, gamma, s.V), dtype=torch.bfloat16, device=self.dev) if gamma else None
@@ -115,8 +118,9 @@ class StepTimer:
 class FullModel:
     """Every layer of a decoder shape resident on one GPU -- its bf16 weights (62 GB for the 32B shape) and the KV
     caches of B branches, each layer its own memory -- and one verify step of the whole stack as one captured graph:
-    per layer the QKV projection, verify_attention on the Q columns of its output, the O projection, gate+up, and
-    down on the first half of gate+up's output (norms, rotary embedding, activation and KV append are outside this
+    per layer the QKV projection, kv_append of its K and V columns to the caches, verify_attention on its Q columns, the
+    O projection, gate+up, and
+    down on the first half of gate+up's output (norms, rotary embedding and activation are outside this
     library, so the values that flow are not a language model's; the shapes, the memory traffic and the launch
     sequence are), then the LM head and the acceptance from logits.  Replaying the graph gives the step's device
     time with the gaps between launches and with nothing left in a cache by an earlier use of the same weights:
@@ -143,7 +147,8 @@ class FullModel:
         z = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16, device=self.dev)
         self.h = bf(M, s.hidden)
         self.qkv, self.attn, self.o, self.gu = z(M, qkv_n), z(B, R, s.Hq, s.D), z(M, s.hidden), z(M, 2 * s.mlp)
-        self.q_view = self.qkv.view(B, R, s.Hq + 2 * s.Hkv, s.D)[:, :, :s.Hq]
+        heads = self.qkv.view(B, R, s.Hq + 2 * s.Hkv, s.D)
+        self.q_view, self.k_view, self.v_view = heads[:, :, :s.Hq], heads[:, :, s.Hq:s.Hq + s.Hkv], heads[:, :, s.Hq + s.Hkv:]
         self.zt = z(B, R, s.V)
         self.zd = bf(B, gamma, s.V) if gamma else None
         self.draft = torch.zeros((B, gamma), dtype=torch.int32, device=self.dev) if gamma else None
@@ -166,6 +171,7 @@ class FullModel:
         h = self.h
         for L in self.layers:
             binding.skinny_gemm(h, L["qkv"], out=self.qkv, workspace=self.ws_gemm)
+            binding.kv_append(self.k_view, self.v_view, L["Kpriv"], L["Vpriv"], self.priv_len)
             binding.verify_attention(self.q_view, L["Kpre"], L["Vpre"], L["Kpriv"], L["Vpriv"], self.priv_len,
                                      out=self.attn, workspace=self.ws_attn)
             binding.skinny_gemm(self.attn.view(M, s.Hq * s.D), L["o"], out=self.o, workspace=self.ws_gemm)

@@ -133,6 +133,18 @@ def test_widenings_are_rejected_before_any_launch(lib):
     assert gm(64, 512, 512, ctypes.c_void_p(4096 + 8), 512, one, 512, one, 512, one, big, None) == -2
     assert gm(64, 512, 512, one, 512, one, 512, one, 512, one, 16, None) == -4
     assert gm(0, 512, 512, one, 512, one, 512, one, 512, one, big, None) == -2
+    ka = lambda B, k, H, D, dt, kn, vn, sb, sr, sh, kp, vp_, pb, ph, pt, Lmax, pl: lib.kv_append(
+        B, k, H, D, dt, kn, vn, sb, sr, sh, kp, vp_, pb, ph, pt, Lmax, pl, None)
+    ok = (4, 3, 8, 128, 1, one, one, 4 * 8 * 128, 8 * 128, 128, one, one, 8 * 4096 * 128, 4096 * 128, 128, 4096, one)
+    bad = lambda **kw: ka(*[kw.get(n, v) for n, v in zip(
+        ("B", "k", "H", "D", "dt", "kn", "vn", "sb", "sr", "sh", "kp", "vp", "pb", "ph", "pt", "Lmax", "pl"), ok)])
+    assert bad(kn=None) == -1 and bad(vp=None) == -1 and bad(pl=None) == -1
+    assert bad(dt=7) == -3
+    assert bad(B=0) == -2 and bad(k=-1) == -2 and bad(H=0) == -2
+    assert bad(D=4) == -2                                  # a bf16 row of 8 bytes: not a multiple of 16
+    assert bad(Lmax=3) == -2                               # shorter than the k + 1 new tokens
+    assert bad(sh=120) == -2 and bad(pt=100) == -2         # strides that are not multiples of 16 bytes, or shorter than a row
+    assert bad(kp=ctypes.c_void_p(4096 + 8)) == -2         # misaligned cache
 
 
 def test_kernel_timer_host_side(lib):

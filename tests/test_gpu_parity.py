@@ -512,6 +512,46 @@ def test_confidence_vote(lotts, oracle, N, B, T):
                 assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), (wm, sm)
 
 
+# ---------------------------------------------------------------------------- cache append
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_kv_append_matches_the_oracle_bit_for_bit(lotts, oracle, dtype):
+    """The new tokens' K and V, taken as strided views out of a projection-shaped matrix, land at the tail of every
+    branch's private cache (ragged lengths, one branch shorter than k + 1 and one beyond the cache: skipped rows);
+    every other element of the caches keeps its bits."""
+    g = S.rng_for(7, 40, salt=len(dtype))
+    B, k, Hq, Hkv, D, Lmax = 5, 3, 6, 2, 128 if dtype == "bf16" else 64, 300
+    R = k + 1
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    qkv = (torch.from_numpy(g.standard_normal((B * R, (Hq + 2 * Hkv) * D), dtype=np.float32)).to(DEV)).to(tdt)
+    v5 = qkv.view(B, R, Hq + 2 * Hkv, D)
+    Knew, Vnew = v5[:, :, Hq:Hq + Hkv], v5[:, :, Hq + Hkv:]
+    Kpriv = torch.from_numpy(g.standard_normal((B, Hkv, Lmax, D), dtype=np.float32)).to(DEV).to(tdt)
+    Vpriv = torch.from_numpy(g.standard_normal((B, Hkv, Lmax, D), dtype=np.float32)).to(DEV).to(tdt)
+    priv_len = np.array([Lmax, R, 77, 2, Lmax + 2], dtype=np.int32)
+    host = (lambda t: t.contiguous().view(torch.uint16).cpu().numpy()) if dtype == "bf16" else (lambda t: t.contiguous().cpu().numpy())
+    Kref, Vref = oracle.kv_append(host(Knew), host(Vnew), host(Kpriv), host(Vpriv), priv_len)
+    lotts.kv_append(Knew, Vnew, Kpriv, Vpriv, to_dev(priv_len))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(Kpriv), Kref) and np.array_equal(host(Vpriv), Vref)
+
+
+def test_append_then_attention_equals_attention_on_a_cache_built_in_place(lotts):
+    """kv_append followed by verify_attention gives the same bits as verify_attention on caches that already held
+    the new rows: the append writes exactly where the attention reads."""
+    cfg = BF.with_(B=4, Hq=8, Hkv=2, k=2, P=40, L=333)
+    d = attn_to_dev(cfg, S.attention_inputs(cfg))
+    want = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], d["priv_len"])
+    R = cfg.k + 1
+    Knew = d["Kpriv"][:, :, cfg.L - R:cfg.L].permute(0, 2, 1, 3).contiguous()   # [B][R][Hkv][D]
+    Vnew = d["Vpriv"][:, :, cfg.L - R:cfg.L].permute(0, 2, 1, 3).contiguous()
+    K2, V2 = d["Kpriv"].clone(), d["Vpriv"].clone()
+    K2[:, :, cfg.L - R:cfg.L] = 0
+    V2[:, :, cfg.L - R:cfg.L] = 0
+    lotts.kv_append(Knew, Vnew, K2, V2, d["priv_len"])
+    got = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], K2, V2, d["priv_len"])
+    assert torch.equal(K2, d["Kpriv"]) and torch.equal(V2, d["Vpriv"]) and torch.equal(got, want)
+
+
 # ---------------------------------------------------------------------------- weight GEMM of the verify forward
 @pytest.mark.parametrize("M,N,K", [
     (64, 512, 1024), (40, 136, 256), (5, 8, 128), (1, 1000, 384), (128, 256, 512), (97, 264, 640),

@@ -14,6 +14,7 @@ import test_oracle_accept as TA
 import test_oracle_attention as TT
 import test_oracle_confidence as TC
 import test_oracle_gemm as TG
+import test_oracle_kv_append as TK
 import test_oracle_logits as TL
 import test_oracle_vote as TV
 
@@ -37,10 +38,18 @@ BATTERY = {
                TL.test_rollback_keeps_exactly_the_verified_tokens],
     "confidence": [TC.test_hand_cases, TC.test_against_dictionary, TC.test_equal_confidences_reduce_to_majority_voting],
     "gemm": [TG.test_matches_numpy_matmul, TG.test_identity_and_orientation],
+    "append": [TK.test_rows_land_at_the_tail_and_nothing_else_moves, TK.test_positions_outside_the_cache_are_skipped,
+               TK.test_the_appended_keys_are_the_ones_each_new_row_sees_last],
 }
 
 # (area, what is planted, text to find, replacement)
 MUTATIONS = [
+    ("append", "new tokens one position late", "const int64_t t = (int64_t)priv_len[b] - R + r;",
+     "const int64_t t = (int64_t)priv_len[b] - R + r + 1;"),
+    ("append", "values written where keys go", "memcpy((char *)Vpriv + dst, (const char *)Vnew + src, row);",
+     "memcpy((char *)Kpriv + dst, (const char *)Vnew + src, row);"),
+    ("append", "heads and rows of the new tokens swapped", "const size_t src = (((size_t)b * R + r) * Hkv + h) * row;",
+     "const size_t src = (((size_t)b * Hkv + h) * R + r) * row;"),
     ("attention", "causal window one key too long", "const int n_priv = Lb - k + i;", "const int n_priv = Lb - k + i + 1;"),
     ("attention", "causal window ignores the row index", "const int n_priv = Lb - k + i;", "const int n_priv = Lb - k;"),
     ("attention", "interleaved instead of contiguous GQA grouping", "const int g = h / G;", "const int g = h % Hkv;"),
@@ -88,7 +97,7 @@ class BrokenOracle:
         import oracle.oracle as real
         self._real, self._lib = real, lib
         for name in ("verify_attention", "spec_accept", "majority_vote", "spec_accept_logits", "logit_weights",
-                     "confidence_vote", "skinny_gemm"):
+                     "confidence_vote", "skinny_gemm", "kv_append"):
             setattr(self, name, self._wrap(getattr(real, name)))
 
     def _wrap(self, fn):
