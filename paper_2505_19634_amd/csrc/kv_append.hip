@@ -25,12 +25,15 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
     const int h = (int)(j % p.Hkv);
     j /= p.Hkv;
     const int r = (int)(j % p.R), b = (int)(j / p.R);
+    // the source does not depend on the length: its loads go out together with the length's, one latency for all
+    const long long src = b * p.new_b + r * p.new_r + h * p.new_h + c * 16LL;
+    const a_u32x4 kv = *reinterpret_cast<const a_u32x4*>(p.Knew + src);
+    const a_u32x4 vv = *reinterpret_cast<const a_u32x4*>(p.Vnew + src);
     const int t = p.priv_len[b] - p.R + r;  // position of new token r in the branch's private cache
     if (t < 0 || t >= p.Lmax) return;
-    const long long src = b * p.new_b + r * p.new_r + h * p.new_h + c * 16LL;
     const long long dst = b * p.priv_b + h * p.priv_h + t * p.priv_t + c * 16LL;
-    *reinterpret_cast<a_u32x4*>(p.Kpriv + dst) = *reinterpret_cast<const a_u32x4*>(p.Knew + src);
-    *reinterpret_cast<a_u32x4*>(p.Vpriv + dst) = *reinterpret_cast<const a_u32x4*>(p.Vnew + src);
+    *reinterpret_cast<a_u32x4*>(p.Kpriv + dst) = kv;
+    *reinterpret_cast<a_u32x4*>(p.Vpriv + dst) = vv;
 }
 
 }  // namespace lotts
