@@ -450,6 +450,18 @@ def main() -> int:
                                                            P(cs), sh), 50, 1)
     out["confidence_vote"] = {"ms": cv_ms, "kernel_ms": cv_kern[0], "scores_per_branch": Tc, "mode": "avg-vote"}
 
+    # cache append of the step's new tokens: K and V columns of a QKV-projection-shaped matrix to the tails of the
+    # private caches of input set 0
+    heads = torch.randn((cfg.B, cfg.R, cfg.Hq + 2 * cfg.Hkv, cfg.D), generator=gen, device=dev).to(sets[0]["Kpriv"].dtype)
+    kn, vn = heads[:, :, cfg.Hq:cfg.Hq + cfg.Hkv], heads[:, :, cfg.Hq + cfg.Hkv:]
+    kp, vp_ = sets[0]["Kpriv"].clone(), sets[0]["Vpriv"].clone()
+    ka_dt = binding.LOTTS_BF16 if kp.dtype == torch.bfloat16 else binding.LOTTS_F32
+    ka_ms, ka_kern = time_op(lambda i: lib.kv_append(cfg.B, cfg.k, cfg.Hkv, cfg.D, ka_dt, P(kn), P(vn), kn.stride(0),
+                                                     kn.stride(1), kn.stride(2), P(kp), P(vp_), kp.stride(0), kp.stride(1),
+                                                     kp.stride(2), kp.shape[2], P(sets[0]["priv_len"]), sh), 50, 1)
+    out["kv_append"] = {"ms": ka_ms, "kernel_ms": ka_kern[0], "bytes_moved": 2 * 2 * cfg.B * cfg.R * cfg.Hkv * cfg.D * kp.element_size()}
+    del heads, kp, vp_
+
     # weight GEMMs of one 32B-shaped decoder layer for the step's M = B * (k + 1) tokens (hidden 5120,
     # 40/8 heads of 128, MLP 27648): QKV, O, gate+up, down.  Weight copies are rotated like the KV sets.
     Mg = args.gemm_tokens if 1 <= args.gemm_tokens <= 256 else min(cfg.B * cfg.R, 256)
