@@ -460,8 +460,9 @@ def test_accept_logits_against_the_probability_oracle(lotts, oracle):
 
 
 def test_multi_step_decode_loop_stays_on_the_device(lotts, oracle):
-    """Several verify steps enqueued back to back with no host round trip: attention over each branch's current
-    cache, acceptance from logits, and the rollback that tells the next step where each branch's cache ends.
+    """Several verify steps enqueued back to back with no host round trip: the step's new K and V rows appended at
+    each branch's tail, attention over each branch's current cache, acceptance from logits, and the rollback that
+    tells the next step where each branch's cache ends (its append then overwrites the rejected drafts' rows).
     Branches drift apart in length as they accept different numbers of drafts; every step is checked."""
     cfg = BF.with_(B=6, P=96, L=640, k=3, V=5000)
     steps = 5
@@ -469,20 +470,26 @@ def test_multi_step_decode_loop_stays_on_the_device(lotts, oracle):
     d = attn_to_dev(cfg, a)
     cache0 = np.array([10, 100, 200, 37, 0, 300], dtype=np.int32)   # valid private tokens before the first step
     logits = [logit_inputs(cfg, 0.8, salt=s, bf16=True) for s in range(steps)]
+    g = S.rng_for(3, 41)
+    new_rows = [tuple(S.f32_to_bf16_bits((0.5 * g.standard_normal((cfg.B, cfg.k + 1, cfg.Hkv, cfg.D))).astype(np.float32))
+                      for _ in range(2)) for _ in range(steps)]
     print("multi-step loop", cfg, flush=True)
     pl_dev = to_dev(cache0 + cfg.k + 1)
     got = []
     for s in range(steps):
         zt, zd, draft, u = logits[s]
+        lotts.kv_append(to_dev(new_rows[s][0], True), to_dev(new_rows[s][1], True), d["Kpriv"], d["Vpriv"], pl_dev)
         O = lotts.verify_attention(d["Q"], d["Kpre"], d["Vpre"], d["Kpriv"], d["Vpriv"], pl_dev)
         n, t = lotts.spec_accept_logits(to_dev(zt, True), to_dev(zd, True), to_dev(draft), to_dev(u), priv_len=pl_dev)
         got.append((O.clone(), n.clone(), t.clone(), pl_dev.clone()))
         pl_dev += cfg.k + 1                                          # the next step appends its k + 1 new tokens
     torch.cuda.synchronize()
     pl = (cache0 + cfg.k + 1).astype(np.int32)
+    Kc, Vc = a["Kpriv"], a["Vpriv"]
     for s in range(steps):
         zt, zd, draft, u = logits[s]
-        Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], a["Kpriv"], a["Vpriv"], pl)
+        Kc, Vc = oracle.kv_append(new_rows[s][0], new_rows[s][1], Kc, Vc, pl)
+        Oref, _ = oracle.verify_attention(a["Q"], a["Kpre"], a["Vpre"], Kc, Vc, pl)
         n_ref, t_ref = oracle.spec_accept_logits(zt, zd, draft, u, priv_len=pl)
         O, n, t, pl_after = got[s]
         e_abs, e_fro, _ = attn_errors(O, Oref)
@@ -491,6 +498,7 @@ def test_multi_step_decode_loop_stays_on_the_device(lotts, oracle):
         assert np.array_equal(pl_after.cpu().numpy(), pl), s
         pl = (pl + cfg.k + 1).astype(np.int32)
     assert len(set((pl - cache0).tolist())) > 1                      # the branches did drift apart
+    assert np.array_equal(d["Kpriv"].view(torch.uint16).cpu().numpy(), Kc)   # the caches went through the same history
 
 
 # ---------------------------------------------------------------------------- confidence-weighted vote
